@@ -1,0 +1,159 @@
+/*
+ * ubp.h - C ABI of the unaligned block-pruned (UBP) sparse x dense product for one
+ *         AMD MI355X (gfx950).
+ *
+ * The operation is the inference computation of a layer pruned with unaligned
+ * block-wise pruning (paper: "Realizing Unaligned Block-wise Pruning for DNN
+ * Acceleration on Mobile Devices", Sections 3.1, 3.3 and 4.2):
+ *
+ *      Y[M x N] = W_ubp[M x K] * X[K x N]
+ *
+ * W_ubp keeps only the weights inside non-overlapping dense bh x bw blocks whose
+ * top-left origins (r, c) are arbitrary - not multiples of the block size (Section 3.1;
+ * the paper's block is bh x 1, this library also takes bw > 1).  X holds one input
+ * channel per row and the pixels (x batch) contiguously; Y likewise for output channels
+ * (the O = W * I orientation of Section 3.3).
+ *
+ * All functions return a ubp_status; none throws, aborts or prints.  Unless stated
+ * otherwise pointers are HOST pointers, the caller owns every buffer it passes in, and
+ * the library owns only what ubp_pack returns through `out`.
+ */
+#ifndef UBP_H
+#define UBP_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    UBP_OK = 0,
+    UBP_ERR_INVALID_ARG = 1,   /* null pointer, non-positive size, bad enum, bad pitch        */
+    UBP_ERR_OUT_OF_BOUNDS = 2, /* a block does not lie inside the M x K matrix                 */
+    UBP_ERR_OVERLAP = 3,       /* two blocks share a cell (includes duplicates)                */
+    UBP_ERR_UNSUPPORTED = 4,   /* valid request this build has no kernel for                   */
+    UBP_ERR_INFEASIBLE = 5,    /* ubp_select_reference could not place the requested blocks    */
+    UBP_ERR_ALLOC = 6,         /* host or device allocation failed                             */
+    UBP_ERR_DEVICE = 7         /* a HIP call failed, or no usable device                       */
+} ubp_status;
+
+typedef enum { UBP_F32 = 0, UBP_F16 = 1, UBP_BF16 = 2 } ubp_dtype;
+
+/* Top-left origin of one kept block, 0-based: it covers rows r..r+bh-1, columns c..c+bw-1. */
+typedef struct { int32_t r, c; } ubp_block;
+
+/* Packed weights: the canonical host arrays of Section 4.2 plus device-side copies. Opaque. */
+typedef struct ubp_packed ubp_packed;
+
+#define UBP_HOST_ONLY (-1)
+
+/*
+ * Number of kept blocks for a target density: floor(M*K*density / (bh*bw) + 1e-9), the
+ * count rule m = floor(b (1 - p) / N) of Section 3.1 with density = 1 - p.  Returns -1 on
+ * bad arguments.
+ */
+int64_t ubp_target_block_count(int32_t M, int32_t K, int32_t bh, int32_t bw, double density);
+
+/*
+ * Test-mask generator (host only, deterministic in all arguments): a valid unaligned
+ * block list with ubp_target_block_count() blocks, satisfying the constraints of Eq. 2
+ * (no overlap) and the edge rule of Eq. 1 (no block crosses the matrix border).
+ *   mode 0: seeded rejection sampling of uniform origins in [0, M-bh] x [0, K-bw].
+ *   mode 1: per-stripe block counts follow a capped Zipf law with exponent zipf_s over
+ *           stripes of bh start rows (heavy stripes scattered by a seeded permutation),
+ *           then rejection sampling inside each stripe.
+ * RNG: SplitMix64 seeded with `seed`; bounded draws by rejection (unbiased).
+ * out: caller-allocated array of `capacity` blocks; *out_nb receives the count; the
+ * list is sorted by (r, c).  UBP_ERR_INVALID_ARG if capacity is too small (then *out_nb
+ * still receives the needed count), UBP_ERR_INFEASIBLE if sampling does not terminate.
+ */
+ubp_status ubp_select_reference(int32_t M, int32_t K, int32_t bh, int32_t bw, double density,
+                                uint64_t seed, int32_t mode, double zipf_s,
+                                ubp_block *out, int64_t capacity, int64_t *out_nb);
+
+/*
+ * Offline weight transform (Section 4.2, "performed offline"): dense W + block list ->
+ * the WROS sparse format, and, unless device == UBP_HOST_ONLY, its upload to that HIP
+ * device (ordinal) together with the kernel's private re-layouts.
+ *
+ *   W_host : row-major M x K, leading dimension ldw (elements, >= K), element type dtype.
+ *            Only the cells inside blocks are read.
+ *   blocks : nb origins in any order.  Rejected, never repaired: UBP_ERR_OUT_OF_BOUNDS if
+ *            r < 0, c < 0, r+bh > M or c+bw > K; UBP_ERR_OVERLAP if two blocks share a cell.
+ *            nb == 0 is legal (Y becomes all zeros).
+ * Canonical arrays (pure functions of the block SET; bits of W copied, never rounded):
+ *   indptr [M-bh+2] int32 : indptr[i] = number of blocks whose start row is < i
+ *                           (one entry per start row 0..M-bh, then the end sentinel);
+ *   indices[nb]     int32 : column origin of each block, blocks ordered by start row and,
+ *                           within a start row, by ascending column origin;
+ *   values [nb*bw*bh]     : values[(b*bw + q)*bh + s] = W[rho][c_b + q] where rho is the
+ *                           row of block b with rho mod bh == s  (weight rotation: the
+ *                           weight of output channel i sits in slot i mod bh).
+ * On error *out is NULL.  Free with ubp_packed_free.
+ */
+ubp_status ubp_pack(const void *W_host, ubp_dtype dtype, int32_t M, int32_t K, int64_t ldw,
+                    int32_t bh, int32_t bw, const ubp_block *blocks, int64_t nb,
+                    int32_t device, ubp_packed **out);
+
+/* Read-only views of the canonical host arrays; valid until ubp_packed_free. */
+const int32_t *ubp_packed_indptr(const ubp_packed *p, int64_t *len);
+const int32_t *ubp_packed_indices(const ubp_packed *p, int64_t *len);
+const void *ubp_packed_values(const ubp_packed *p, int64_t *len_elems);
+
+/*
+ * Y = W_ubp * X on the device the handle was packed for (Sections 3.3 and 4.2: the
+ * output-stationary product; every output element is accumulated in fp32 registers and
+ * written exactly once).
+ *   X_dev : DEVICE pointer, row-major K x N, leading dimension ldx (elements, >= N),
+ *           element type = the handle's dtype.
+ *   Y_dev : DEVICE pointer, row-major M x N, leading dimension ldy (elements, >= N),
+ *           element type y_dtype = UBP_F32 or the handle's dtype (fp32 accumulators are
+ *           rounded to nearest-even once, at the store).  Every element of the M x N
+ *           result is overwritten, rows no block touches with +0.  X and Y must not alias.
+ *   hip_stream : a hipStream_t (NULL = the default stream).  The call only enqueues
+ *           kernels on that stream: it never synchronises, allocates or copies.
+ * N == 0 is a no-op.  Errors: UBP_ERR_INVALID_ARG (null pointer, N < 0, pitch < N,
+ * host-only handle, y_dtype neither fp32 nor the handle's dtype), UBP_ERR_UNSUPPORTED,
+ * UBP_ERR_DEVICE (launch failed).  Nothing is written to Y on error.
+ * Non-finite X: a zero weight the kernel pads with still multiplies X, so Inf/NaN in X can
+ * reach outputs whose exact sum does not contain them.
+ */
+ubp_status ubp_spmm(const ubp_packed *p, const void *X_dev, int64_t ldx, int32_t N,
+                    void *Y_dev, int64_t ldy, ubp_dtype y_dtype, void *hip_stream);
+
+/*
+ * Same product with the kernel choice pinned (tests and tuning).  Fields set to 0 mean
+ * "choose automatically"; an impossible combination returns UBP_ERR_UNSUPPORTED.
+ *   kernel     : 1 = vector-ALU kernel that follows the WROS dataflow literally (any
+ *                dtype, bh <= 16); 2 = MFMA kernel on aligned 16-row stripes (f16 / bf16).
+ *   sub_stripes: MFMA kernel, 16-row stripes per wavefront (1, 2 or 4).
+ *   col_tiles  : MFMA kernel, 16-column tiles per wavefront (2, 4 or 8).
+ *   waves      : wavefronts per workgroup (1..16).
+ *   rows_per_range : WROS kernel, output rows owned by one workgroup row (multiple of bh).
+ */
+typedef struct {
+    int32_t kernel, sub_stripes, col_tiles, waves, rows_per_range, reserved[3];
+} ubp_plan;
+
+ubp_status ubp_spmm_plan(const ubp_packed *p, const void *X_dev, int64_t ldx, int32_t N,
+                         void *Y_dev, int64_t ldy, ubp_dtype y_dtype, void *hip_stream,
+                         const ubp_plan *plan);
+
+/*
+ * Facts about a handle, for reporting.  what: 0 M, 1 K, 2 bh, 3 bw, 4 nb, 5 dtype,
+ * 6 device (-1 host only), 7 bytes of the canonical arrays (values + indptr + indices),
+ * 8 bytes of all device-side copies.  Unknown `what` returns -1.
+ */
+int64_t ubp_packed_info(const ubp_packed *p, int32_t what);
+
+/* Releases host and device memory of the handle (NULL is allowed).  Must not be called
+ * while a ubp_spmm using the handle is still running on the device. */
+void ubp_packed_free(ubp_packed *p);
+
+const char *ubp_status_string(ubp_status s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* UBP_H */

@@ -1,0 +1,7 @@
+"""MI355X-native unaligned block-pruned (UBP) sparse x dense product.
+
+Thin ctypes binding over the C ABI declared in include/ubp.h.  Everything is computed by
+the native library (host packer + HIP kernels); this package only marshals arguments.
+"""
+from .binding import (UBPError, Packed, Plan, load_library, library_path, select_reference,  # noqa: F401
+                      target_block_count, pack, spmm, status_string, DTYPES, EXPORTS)

@@ -1,0 +1,170 @@
+"""ctypes binding of include/ubp.h: same names, argument marshalling only.
+
+The library is loaded from the package directory (libubp.so, built by build.py).  If it is
+missing the import of any entry point fails loudly; there is no fallback path.
+"""
+import ctypes
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libubp.so")
+
+UBP_OK = 0
+UBP_HOST_ONLY = -1
+DTYPES = {"f32": 0, "f16": 1, "bf16": 2}
+_NP_OF = {"f32": np.float32, "f16": np.float16, "bf16": np.uint16}
+EXPORTS = ("ubp_target_block_count", "ubp_select_reference", "ubp_pack", "ubp_packed_indptr",
+           "ubp_packed_indices", "ubp_packed_values", "ubp_spmm", "ubp_spmm_plan", "ubp_packed_info",
+           "ubp_packed_free", "ubp_status_string")
+
+
+class UBPError(RuntimeError):
+    def __init__(self, code, where):
+        self.code = int(code)
+        super().__init__("%s: %s (status %d)" % (where, status_string(code), code))
+
+
+class Plan(ctypes.Structure):
+    """Mirror of ubp_plan; zero fields mean 'choose automatically'."""
+    _fields_ = [("kernel", ctypes.c_int32), ("sub_stripes", ctypes.c_int32), ("col_tiles", ctypes.c_int32),
+                ("waves", ctypes.c_int32), ("rows_per_range", ctypes.c_int32), ("reserved", ctypes.c_int32 * 3)]
+
+
+_lib = None
+
+
+def library_path():
+    return _LIB_PATH
+
+
+def load_library():
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError("native library %s is missing: run `python -m paper_2407_19644_amd.build` "
+                          "(there is no fallback implementation)" % _LIB_PATH)
+    L = ctypes.CDLL(_LIB_PATH)
+    i32, i64, u64, dbl, vp = ctypes.c_int32, ctypes.c_int64, ctypes.c_uint64, ctypes.c_double, ctypes.c_void_p
+    pi64 = ctypes.POINTER(i64)
+    L.ubp_target_block_count.argtypes = [i32, i32, i32, i32, dbl]
+    L.ubp_target_block_count.restype = i64
+    L.ubp_select_reference.argtypes = [i32, i32, i32, i32, dbl, u64, i32, dbl, vp, i64, pi64]
+    L.ubp_select_reference.restype = ctypes.c_int
+    L.ubp_pack.argtypes = [vp, ctypes.c_int, i32, i32, i64, i32, i32, vp, i64, i32, ctypes.POINTER(vp)]
+    L.ubp_pack.restype = ctypes.c_int
+    for f in (L.ubp_packed_indptr, L.ubp_packed_indices, L.ubp_packed_values):
+        f.argtypes = [vp, pi64]
+        f.restype = vp
+    L.ubp_spmm.argtypes = [vp, vp, i64, i32, vp, i64, ctypes.c_int, vp]
+    L.ubp_spmm.restype = ctypes.c_int
+    L.ubp_spmm_plan.argtypes = [vp, vp, i64, i32, vp, i64, ctypes.c_int, vp, ctypes.POINTER(Plan)]
+    L.ubp_spmm_plan.restype = ctypes.c_int
+    L.ubp_packed_info.argtypes = [vp, i32]
+    L.ubp_packed_info.restype = i64
+    L.ubp_packed_free.argtypes = [vp]
+    L.ubp_packed_free.restype = None
+    L.ubp_status_string.argtypes = [ctypes.c_int]
+    L.ubp_status_string.restype = ctypes.c_char_p
+    _lib = L
+    return L
+
+
+def status_string(code):
+    return load_library().ubp_status_string(int(code)).decode()
+
+
+def target_block_count(M, K, bh, bw, density):
+    return int(load_library().ubp_target_block_count(M, K, bh, bw, float(density)))
+
+
+def select_reference(M, K, bh, bw, density, seed, mode=0, zipf_s=0.0):
+    """ubp_select_reference -> int32 array [nb, 2] of (r, c), sorted."""
+    L = load_library()
+    nb = ctypes.c_int64(0)
+    need = L.ubp_target_block_count(M, K, bh, bw, float(density))
+    if need < 0:
+        raise UBPError(1, "ubp_select_reference")
+    out = np.zeros((max(int(need), 1), 2), dtype=np.int32)
+    rc = L.ubp_select_reference(M, K, bh, bw, float(density), int(seed), int(mode), float(zipf_s),
+                                out.ctypes.data, int(need), ctypes.byref(nb))
+    if rc != UBP_OK:
+        raise UBPError(rc, "ubp_select_reference")
+    return out[:nb.value].copy()
+
+
+class Packed:
+    """Owner of a ubp_packed handle."""
+
+    def __init__(self, handle, dtype):
+        self._h = ctypes.c_void_p(handle)
+        self.dtype = dtype
+
+    @property
+    def handle(self):
+        if not self._h:
+            raise ValueError("handle already freed")
+        return self._h
+
+    def info(self, what):
+        return int(load_library().ubp_packed_info(self.handle, what))
+
+    def _view(self, fn, np_dtype):
+        n = ctypes.c_int64(0)
+        ptr = fn(self.handle, ctypes.byref(n))
+        if n.value == 0:
+            return np.zeros(0, dtype=np_dtype)
+        buf = (ctypes.c_char * (n.value * np.dtype(np_dtype).itemsize)).from_address(ptr)
+        return np.frombuffer(buf, dtype=np_dtype).copy()
+
+    @property
+    def indptr(self):
+        return self._view(load_library().ubp_packed_indptr, np.int32)
+
+    @property
+    def indices(self):
+        return self._view(load_library().ubp_packed_indices, np.int32)
+
+    @property
+    def values(self):
+        return self._view(load_library().ubp_packed_values, _NP_OF[self.dtype])
+
+    def free(self):
+        if self._h:
+            load_library().ubp_packed_free(self._h)
+            self._h = ctypes.c_void_p(None)
+
+    def __del__(self):
+        try:
+            self.free()
+        except Exception:
+            pass
+
+
+def pack(W_host, dtype, bh, bw, blocks, device=UBP_HOST_ONLY):
+    """ubp_pack.  W_host: 2-D numpy array holding the element type's bits (float32, float16,
+    or uint16 for bf16), row-major; blocks: [nb, 2] (r, c).  device: HIP ordinal or -1."""
+    L = load_library()
+    W = np.asarray(W_host)
+    if W.ndim != 2 or W.dtype != _NP_OF[dtype] or W.strides[1] != W.itemsize or W.strides[0] % W.itemsize:
+        raise ValueError("W must be a row-major 2-D array of %s" % _NP_OF[dtype].__name__)
+    b = np.ascontiguousarray(np.asarray(blocks, dtype=np.int32).reshape(-1, 2))
+    out = ctypes.c_void_p(None)
+    rc = L.ubp_pack(W.ctypes.data, DTYPES[dtype], W.shape[0], W.shape[1], W.strides[0] // W.itemsize,
+                    bh, bw, b.ctypes.data, b.shape[0], int(device), ctypes.byref(out))
+    if rc != UBP_OK:
+        raise UBPError(rc, "ubp_pack")
+    return Packed(out.value, dtype)
+
+
+def spmm(packed, X_ptr, ldx, N, Y_ptr, ldy, y_dtype, stream=0, plan=None):
+    """ubp_spmm / ubp_spmm_plan with raw DEVICE pointers (e.g. torch tensors' data_ptr())."""
+    L = load_library()
+    if plan is None:
+        rc = L.ubp_spmm(packed.handle, X_ptr, ldx, N, Y_ptr, ldy, DTYPES[y_dtype], stream)
+    else:
+        rc = L.ubp_spmm_plan(packed.handle, X_ptr, ldx, N, Y_ptr, ldy, DTYPES[y_dtype], stream, ctypes.byref(plan))
+    if rc != UBP_OK:
+        raise UBPError(rc, "ubp_spmm")

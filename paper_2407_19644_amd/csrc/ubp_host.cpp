@@ -1,0 +1,414 @@
+// Host side of the UBP library: test-mask generator, offline weight transform
+// (validation, canonical ordering, indptr / indices, weight rotation) and the
+// accessors of the handle.  No device code here.
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <new>
+#include <numeric>
+
+#include "ubp_internal.h"
+
+namespace {
+
+// ---------------------------------------------------------------- RNG (SplitMix64)
+struct SplitMix64 {
+    uint64_t s;
+    explicit SplitMix64(uint64_t seed) : s(seed) {}
+    uint64_t next() {
+        s += 0x9E3779B97F4A7C15ull;
+        uint64_t z = s;
+        z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+        z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+        return z ^ (z >> 31);
+    }
+    // uniform in [0, n), unbiased: reject words at or above floor(2^64 / n) * n
+    uint64_t bounded(uint64_t n) {
+        // floor(2^64 / n) computed without 128-bit arithmetic
+        uint64_t q = (~0ull) / n;
+        if ((~0ull) % n == n - 1) ++q; // 2^64 is a multiple of n
+        uint64_t limit = q * n;        // wraps to 0 exactly when 2^64 itself is the limit
+        for (;;) {
+            uint64_t x = next();
+            if (limit == 0 || x < limit) return x % n;
+        }
+    }
+};
+
+// Occupancy bitmap of the M x K matrix.
+struct CellMap {
+    int64_t K;
+    std::vector<uint64_t> bits;
+    CellMap(int64_t M, int64_t K_) : K(K_), bits((size_t)((M * K_ + 63) / 64), 0) {}
+    bool get(int64_t r, int64_t c) const {
+        int64_t t = r * K + c;
+        return (bits[(size_t)(t >> 6)] >> (t & 63)) & 1;
+    }
+    void set(int64_t r, int64_t c) {
+        int64_t t = r * K + c;
+        bits[(size_t)(t >> 6)] |= 1ull << (t & 63);
+    }
+    bool any(int32_t r, int32_t c, int32_t bh, int32_t bw) const {
+        for (int32_t i = 0; i < bh; ++i)
+            for (int32_t j = 0; j < bw; ++j)
+                if (get(r + i, c + j)) return true;
+        return false;
+    }
+    void paint(int32_t r, int32_t c, int32_t bh, int32_t bw) {
+        for (int32_t i = 0; i < bh; ++i)
+            for (int32_t j = 0; j < bw; ++j) set(r + i, c + j);
+    }
+};
+
+bool block_less(const ubp_block &a, const ubp_block &b) { return a.r != b.r ? a.r < b.r : a.c < b.c; }
+
+// Capped Zipf targets per rank: t = min(cap, lambda * rank^-s), sum == nb, integers by
+// largest remainder (ties to the lower rank).
+bool zipf_targets(int64_t nb, int64_t S, int64_t cap, double s, std::vector<int64_t> &t) {
+    if (nb > S * cap) return false;
+    std::vector<double> w((size_t)S);
+    for (int64_t j = 0; j < S; ++j) w[(size_t)j] = std::pow((double)(j + 1), -s);
+    std::vector<char> capped((size_t)S, 0);
+    double remaining = (double)nb, lam = 0.0;
+    for (;;) {
+        double wsum = 0.0;
+        for (int64_t j = 0; j < S; ++j)
+            if (!capped[(size_t)j]) wsum += w[(size_t)j];
+        if (wsum <= 0.0) break;
+        lam = remaining / wsum;
+        bool changed = false;
+        for (int64_t j = 0; j < S; ++j)
+            if (!capped[(size_t)j] && lam * w[(size_t)j] > (double)cap) {
+                capped[(size_t)j] = 1;
+                remaining -= (double)cap;
+                changed = true;
+            }
+        if (!changed) break;
+    }
+    std::vector<double> real((size_t)S), frac((size_t)S);
+    t.assign((size_t)S, 0);
+    int64_t sum = 0;
+    for (int64_t j = 0; j < S; ++j) {
+        real[(size_t)j] = capped[(size_t)j] ? (double)cap : lam * w[(size_t)j];
+        t[(size_t)j] = (int64_t)std::floor(real[(size_t)j]);
+        frac[(size_t)j] = real[(size_t)j] - (double)t[(size_t)j];
+        sum += t[(size_t)j];
+    }
+    std::vector<int64_t> order((size_t)S);
+    std::iota(order.begin(), order.end(), 0);
+    std::stable_sort(order.begin(), order.end(),
+                     [&](int64_t a, int64_t b) { return frac[(size_t)a] > frac[(size_t)b]; });
+    int64_t left = nb - sum;
+    for (int64_t i = 0; left > 0; ++i) {
+        int64_t j = order[(size_t)(i % S)];
+        if (t[(size_t)j] < cap) {
+            ++t[(size_t)j];
+            --left;
+        }
+    }
+    return true;
+}
+
+} // namespace
+
+extern "C" {
+
+int64_t ubp_target_block_count(int32_t M, int32_t K, int32_t bh, int32_t bw, double density) {
+    if (M < 1 || K < 1 || bh < 1 || bw < 1 || bh > M || bw > K || !(density >= 0.0 && density <= 1.0)) return -1;
+    return (int64_t)std::floor(((double)M * (double)K * density) / (double)(bh * bw) + 1e-9);
+}
+
+ubp_status ubp_select_reference(int32_t M, int32_t K, int32_t bh, int32_t bw, double density, uint64_t seed,
+                                int32_t mode, double zipf_s, ubp_block *out, int64_t capacity, int64_t *out_nb) {
+    if (!out_nb) return UBP_ERR_INVALID_ARG;
+    *out_nb = 0;
+    int64_t nb = ubp_target_block_count(M, K, bh, bw, density);
+    if (nb < 0 || (mode != 0 && mode != 1)) return UBP_ERR_INVALID_ARG;
+    *out_nb = nb;
+    if (capacity < nb || (nb > 0 && !out)) return UBP_ERR_INVALID_ARG;
+    try {
+        SplitMix64 rng(seed);
+        CellMap occ(M, K);
+        const int64_t nr = (int64_t)M - bh + 1, nc = (int64_t)K - bw + 1;
+        const int64_t max_attempts = 2000 * nb + 100000;
+        int64_t got_total = 0;
+        auto fill = [&](int64_t count, int64_t r_base, int64_t r_span) -> bool {
+            int64_t attempts = 0, got = 0;
+            while (got < count) {
+                if (++attempts > max_attempts) return false;
+                int32_t r = (int32_t)(r_base + (int64_t)rng.bounded((uint64_t)r_span));
+                int32_t c = (int32_t)rng.bounded((uint64_t)nc);
+                if (occ.any(r, c, bh, bw)) continue;
+                occ.paint(r, c, bh, bw);
+                out[got_total++] = ubp_block{r, c};
+                ++got;
+            }
+            return true;
+        };
+        if (mode == 0) {
+            if (!fill(nb, 0, nr)) return UBP_ERR_INFEASIBLE;
+        } else {
+            const int64_t S = (nr + bh - 1) / bh;
+            const int64_t cap = (int64_t)std::floor(0.375 * (double)K / (double)bw);
+            std::vector<int64_t> t_rank;
+            if (!zipf_targets(nb, S, cap, zipf_s, t_rank)) return UBP_ERR_INFEASIBLE;
+            std::vector<int64_t> perm((size_t)S);
+            std::iota(perm.begin(), perm.end(), 0);
+            for (int64_t i = S - 1; i > 0; --i) std::swap(perm[(size_t)i], perm[(size_t)rng.bounded((uint64_t)i + 1)]);
+            std::vector<int64_t> t_stripe((size_t)S, 0);
+            for (int64_t rank = 0; rank < S; ++rank) t_stripe[(size_t)perm[(size_t)rank]] = t_rank[(size_t)rank];
+            for (int64_t st = 0; st < S; ++st) {
+                int64_t rows = std::min<int64_t>(bh, nr - bh * st);
+                if (!fill(t_stripe[(size_t)st], bh * st, rows)) return UBP_ERR_INFEASIBLE;
+            }
+        }
+        std::sort(out, out + nb, block_less);
+    } catch (const std::bad_alloc &) {
+        return UBP_ERR_ALLOC;
+    }
+    return UBP_OK;
+}
+
+ubp_status ubp_pack(const void *W_host, ubp_dtype dtype, int32_t M, int32_t K, int64_t ldw, int32_t bh, int32_t bw,
+                    const ubp_block *blocks, int64_t nb, int32_t device, ubp_packed **out) {
+    if (!out) return UBP_ERR_INVALID_ARG;
+    *out = nullptr;
+    if (M < 1 || K < 1 || bh < 1 || bw < 1 || nb < 0 || ldw < K || (nb > 0 && (!blocks || !W_host))) return UBP_ERR_INVALID_ARG;
+    if (dtype != UBP_F32 && dtype != UBP_F16 && dtype != UBP_BF16) return UBP_ERR_INVALID_ARG;
+    if (device < UBP_HOST_ONLY) return UBP_ERR_INVALID_ARG;
+    ubp_packed *p = nullptr;
+    try {
+        // a1: bounds (the edge rule of Eq. 1), then pairwise disjointness (Eq. 2) on a cell bitmap
+        for (int64_t b = 0; b < nb; ++b) {
+            const ubp_block &k = blocks[b];
+            if (k.r < 0 || k.c < 0 || (int64_t)k.r + bh > M || (int64_t)k.c + bw > K) return UBP_ERR_OUT_OF_BOUNDS;
+        }
+        {
+            CellMap occ(M, K);
+            for (int64_t b = 0; b < nb; ++b) {
+                if (occ.any(blocks[b].r, blocks[b].c, bh, bw)) return UBP_ERR_OVERLAP;
+                occ.paint(blocks[b].r, blocks[b].c, bh, bw);
+            }
+        }
+        p = new ubp_packed();
+        p->M = M; p->K = K; p->bh = bh; p->bw = bw; p->nb = nb; p->dtype = dtype;
+        // canonical order: start row, then column origin
+        std::vector<ubp_block> sorted(blocks, blocks + nb);
+        std::sort(sorted.begin(), sorted.end(), block_less);
+        // a2: metadata. indptr is indexed by START ROW (the tile row index advances by one
+        // row in an unaligned kernel, Section 3.3), valid start rows are 0..M-bh.
+        const int64_t nstart = (int64_t)M - bh + 1;
+        p->indptr.assign((size_t)(nstart > 0 ? nstart + 1 : 1), 0);
+        for (int64_t b = 0; b < nb; ++b) ++p->indptr[(size_t)sorted[(size_t)b].r + 1];
+        for (size_t i = 1; i < p->indptr.size(); ++i) p->indptr[i] += p->indptr[i - 1];
+        p->indices.resize((size_t)nb);
+        // a3: weight rotation (Section 4.2): the weight of matrix row rho goes to slot rho mod bh
+        const int64_t esz = ubp::dtype_size(dtype);
+        p->values.assign((size_t)(nb * bw * bh * esz), 0);
+        const uint8_t *w = static_cast<const uint8_t *>(W_host);
+        for (int64_t b = 0; b < nb; ++b) {
+            const int32_t r = sorted[(size_t)b].r, c = sorted[(size_t)b].c;
+            p->indices[(size_t)b] = c;
+            for (int32_t q = 0; q < bw; ++q)
+                for (int32_t d = 0; d < bh; ++d) {
+                    const int32_t rho = r + d, s = rho % bh;
+                    std::memcpy(&p->values[(size_t)(((b * bw + q) * bh + s) * esz)],
+                                w + ((int64_t)rho * ldw + (c + q)) * esz, (size_t)esz);
+                }
+        }
+        if (dtype != UBP_F32) ubp::build_stripe_layouts(p);
+        if (device != UBP_HOST_ONLY) {
+            p->device = device;
+            ubp_status st = ubp::upload(p);
+            if (st != UBP_OK) {
+                ubp::release_device(p);
+                delete p;
+                return st;
+            }
+        }
+    } catch (const std::bad_alloc &) {
+        if (p) {
+            ubp::release_device(p);
+            delete p;
+        }
+        return UBP_ERR_ALLOC;
+    }
+    *out = p;
+    return UBP_OK;
+}
+
+const int32_t *ubp_packed_indptr(const ubp_packed *p, int64_t *len) {
+    if (!p) return nullptr;
+    if (len) *len = (int64_t)p->indptr.size();
+    return p->indptr.data();
+}
+
+const int32_t *ubp_packed_indices(const ubp_packed *p, int64_t *len) {
+    if (!p) return nullptr;
+    if (len) *len = (int64_t)p->indices.size();
+    return p->indices.data();
+}
+
+const void *ubp_packed_values(const ubp_packed *p, int64_t *len_elems) {
+    if (!p) return nullptr;
+    if (len_elems) *len_elems = p->nb * p->bw * p->bh;
+    return p->values.data();
+}
+
+int64_t ubp_packed_info(const ubp_packed *p, int32_t what) {
+    if (!p) return -1;
+    switch (what) {
+    case 0: return p->M;
+    case 1: return p->K;
+    case 2: return p->bh;
+    case 3: return p->bw;
+    case 4: return p->nb;
+    case 5: return (int64_t)p->dtype;
+    case 6: return p->device;
+    case 7: return (int64_t)p->values.size() + (int64_t)(p->indptr.size() + p->indices.size()) * 4;
+    case 8: return p->device_bytes;
+    case 10: return p->sg[0].total_mfma;
+    case 11: return p->sg[1].total_mfma;
+    case 12: return p->sg[2].total_mfma;
+    default: return -1;
+    }
+}
+
+void ubp_packed_free(ubp_packed *p) {
+    if (!p) return;
+    ubp::release_device(p);
+    delete p;
+}
+
+const char *ubp_status_string(ubp_status s) {
+    switch (s) {
+    case UBP_OK: return "ok";
+    case UBP_ERR_INVALID_ARG: return "invalid argument";
+    case UBP_ERR_OUT_OF_BOUNDS: return "block out of bounds";
+    case UBP_ERR_OVERLAP: return "blocks overlap";
+    case UBP_ERR_UNSUPPORTED: return "unsupported configuration";
+    case UBP_ERR_INFEASIBLE: return "block selection infeasible";
+    case UBP_ERR_ALLOC: return "allocation failed";
+    case UBP_ERR_DEVICE: return "HIP device error";
+    }
+    return "unknown status";
+}
+
+} // extern "C"
+
+// ---------------------------------------------------------------- private MFMA layout
+namespace ubp {
+
+namespace {
+
+struct Entry {
+    int32_t k;     // column of W == row of X
+    uint32_t mask; // stripes of the row group with a kept weight in this column
+    int32_t slot;  // index into the row group's weight scratch
+};
+
+} // namespace
+
+static void build_one(ubp_packed *p, StripeLayout &L, int G) {
+    const int M = p->M, K = p->K, bh = p->bh, bw = p->bw;
+    const int rgh = kStripe * G;
+    L.G = G;
+    L.nrg = (M + rgh - 1) / rgh;
+    L.nch = (K + kChunkRows - 1) / kChunkRows;
+    L.seg_ptr.assign((size_t)L.nrg * L.nch + 1, 0);
+    L.step_meta.clear();
+    L.lane_rows.clear();
+    L.wfrag.clear();
+    L.total_mfma = 0;
+    const uint16_t *vals = reinterpret_cast<const uint16_t *>(p->values.data());
+    const int32_t nstart = M - bh + 1; // start rows 0..M-bh
+    std::vector<int32_t> colslot((size_t)K, -1);
+    std::vector<Entry> entries;
+    std::vector<uint16_t> wbuf; // [entry slot][rgh]
+    std::vector<int64_t> rg_weight((size_t)L.nrg, 0);
+
+    for (int rg = 0; rg < L.nrg; ++rg) {
+        const int row0 = rg * rgh, row1 = std::min(M, row0 + rgh);
+        entries.clear();
+        wbuf.clear();
+        // blocks whose rows [r, r+bh) meet [row0, row1): start rows in (row0-bh, row1)
+        const int s0 = std::max(0, row0 - bh + 1), s1 = std::min(nstart, row1);
+        for (int i = s0; i < s1; ++i) {
+            for (int32_t b = p->indptr[(size_t)i]; b < p->indptr[(size_t)i + 1]; ++b) {
+                const int32_t c = p->indices[(size_t)b];
+                for (int q = 0; q < bw; ++q) {
+                    const int k = c + q;
+                    int32_t &slot = colslot[(size_t)k];
+                    if (slot < 0) {
+                        slot = (int32_t)entries.size();
+                        entries.push_back(Entry{k, 0u, slot});
+                        wbuf.resize(wbuf.size() + (size_t)rgh, 0);
+                    }
+                    for (int rho = std::max(i, row0); rho < std::min(i + bh, row1); ++rho) {
+                        // rotated storage: row rho of block b lives in slot rho mod bh
+                        wbuf[(size_t)slot * rgh + (rho - row0)] = vals[((int64_t)b * bw + q) * bh + (rho % bh)];
+                        entries[(size_t)slot].mask |= 1u << ((rho - row0) / kStripe);
+                    }
+                }
+            }
+        }
+        for (const Entry &e : entries) colslot[(size_t)e.k] = -1;
+        std::sort(entries.begin(), entries.end(), [](const Entry &a, const Entry &b) {
+            const int ca = a.k / kChunkRows, cb = b.k / kChunkRows;
+            if (ca != cb) return ca < cb;
+            if (a.mask != b.mask) return a.mask < b.mask;
+            return a.k < b.k;
+        });
+        size_t pos = 0;
+        for (int ch = 0; ch < L.nch; ++ch) {
+            L.seg_ptr[(size_t)rg * L.nch + ch] = (int32_t)L.step_meta.size();
+            size_t end = pos;
+            while (end < entries.size() && entries[end].k / kChunkRows == ch) ++end;
+            for (size_t s = pos; s < end; s += kStep) {
+                const size_t n = std::min<size_t>(kStep, end - s);
+                uint32_t mask = 0;
+                for (size_t e = 0; e < n; ++e) mask |= entries[s + e].mask;
+                const uint32_t first_frag = (uint32_t)(L.wfrag.size() / (64 * 8));
+                L.step_meta.push_back((first_frag << 8) | mask);
+                // X rows gathered by this step, chunk-relative; padding repeats the first row
+                int32_t rows[kStep];
+                for (size_t e = 0; e < (size_t)kStep; ++e)
+                    rows[e] = (e < n ? entries[s + e].k : entries[s].k) - ch * kChunkRows;
+                // a lane's two transposed reads fetch entries 8g + t/4 and 8g + 4 + t/4 (t = lane mod 16)
+                for (int lane = 0; lane < 64; ++lane) {
+                    const int g = lane / 16, t = lane % 16;
+                    const uint32_t lo = (uint32_t)rows[8 * g + t / 4], hi = (uint32_t)rows[8 * g + 4 + t / 4];
+                    L.lane_rows.push_back(lo | (hi << 16));
+                }
+                // weight fragments: lane (n = lane mod 16, g = lane / 16) holds row 16*j + n,
+                // entries 8g .. 8g+7
+                for (int j = 0; j < G; ++j) {
+                    if (!(mask & (1u << j))) continue;
+                    for (int lane = 0; lane < 64; ++lane) {
+                        const int g = lane / 16, nrow = lane % 16;
+                        for (int e = 0; e < 8; ++e) {
+                            const size_t idx = (size_t)(8 * g + e);
+                            uint16_t v = 0;
+                            if (idx < n) v = wbuf[(size_t)entries[s + idx].slot * rgh + (kStripe * j + nrow)];
+                            L.wfrag.push_back(v);
+                        }
+                    }
+                    ++L.total_mfma;
+                    ++rg_weight[(size_t)rg];
+                }
+            }
+            pos = end;
+        }
+    }
+    L.seg_ptr[(size_t)L.nrg * L.nch] = (int32_t)L.step_meta.size();
+    L.rg_order.resize((size_t)L.nrg);
+    std::iota(L.rg_order.begin(), L.rg_order.end(), 0);
+    std::stable_sort(L.rg_order.begin(), L.rg_order.end(),
+                     [&](int32_t a, int32_t b) { return rg_weight[(size_t)a] > rg_weight[(size_t)b]; });
+}
+
+void build_stripe_layouts(ubp_packed *p) {
+    for (int s = 0; s < kNumG; ++s) build_one(p, p->sg[s], g_of_slot(s));
+}
+
+} // namespace ubp

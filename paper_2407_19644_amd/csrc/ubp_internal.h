@@ -1,0 +1,77 @@
+// Internal definitions shared by the host-side packer and the HIP launch code.
+#pragma once
+
+#include <cstdint>
+#include <vector>
+
+#include "ubp.h"
+
+namespace ubp {
+
+constexpr int kStripe = 16;     // rows of one MFMA output tile (aligned row stripe)
+constexpr int kStep = 32;       // gathered X rows consumed by one 16x16x32 MFMA
+constexpr int kChunkRows = 256; // X rows staged in LDS per chunk
+constexpr int kNumG = 3;        // layouts are built for 1, 2 and 4 stripes per wavefront
+
+inline int g_of_slot(int slot) { return 1 << slot; }
+
+// Host image of the MFMA kernel's private re-layout of the packed weights, for one
+// choice of G (16-row stripes handled together by one wavefront).
+//
+// Rows are cut into row groups of 16*G aligned rows.  For a row group the columns of W
+// that hold at least one kept weight in it are its "entries"; an entry is one row of X
+// to gather plus the 16*G weights of that column (zero where no block covers the row).
+// Entries are cut by chunk of kChunkRows X rows, ordered inside a chunk by the set of
+// stripes they touch and then by column, and grouped 32 at a time into "steps".
+struct StripeLayout {
+    int G = 0;
+    int nrg = 0;     // row groups
+    int nch = 0;     // chunks of X rows
+    std::vector<int32_t> seg_ptr;    // [nrg*nch + 1] first step of (row group, chunk)
+    std::vector<int32_t> rg_order;   // row groups, heaviest (most MFMAs) first
+    std::vector<uint32_t> step_meta; // [steps] low 8 bits: stripes with nonzero weights; high 24: first fragment
+    std::vector<uint32_t> lane_rows; // [steps*64] per lane: chunk-relative X rows of its two transposed LDS reads
+    std::vector<uint16_t> wfrag;     // [fragments*64*8] weight fragments in MFMA operand order (16-bit patterns)
+    int64_t total_mfma = 0;          // fragments (one per 16-column tile per step and stripe)
+};
+
+struct StripeLayoutDev {
+    int32_t *seg_ptr = nullptr;
+    int32_t *rg_order = nullptr;
+    uint32_t *step_meta = nullptr;
+    uint32_t *lane_rows = nullptr;
+    uint16_t *wfrag = nullptr;
+};
+
+} // namespace ubp
+
+struct ubp_packed {
+    int32_t M = 0, K = 0, bh = 0, bw = 0;
+    int64_t nb = 0;
+    ubp_dtype dtype = UBP_F32;
+    int32_t device = UBP_HOST_ONLY;
+    // canonical arrays (Section 4.2 of the paper)
+    std::vector<int32_t> indptr, indices;
+    std::vector<uint8_t> values; // nb*bw*bh elements of dtype, rotated
+    // private layouts
+    ubp::StripeLayout sg[ubp::kNumG];
+    // device side
+    int32_t *d_indptr = nullptr;
+    int32_t *d_indices = nullptr;
+    float *d_values_f32 = nullptr; // rotated values widened to fp32 (exact)
+    ubp::StripeLayoutDev d_sg[ubp::kNumG];
+    int64_t device_bytes = 0;
+};
+
+namespace ubp {
+
+inline int64_t dtype_size(ubp_dtype d) { return d == UBP_F32 ? 4 : 2; }
+
+// host: builds p->sg[*] from the canonical arrays (16-bit dtypes only)
+void build_stripe_layouts(ubp_packed *p);
+
+// device (defined in the HIP translation unit)
+ubp_status upload(ubp_packed *p);
+void release_device(ubp_packed *p);
+
+} // namespace ubp

@@ -1,0 +1,535 @@
+// Device side of the UBP library for gfx950: upload of the packed weights, the two
+// SpMM kernels and their launch logic.
+//
+//  * wros_kernel  - vector-ALU kernel that follows the paper's WROS dataflow literally
+//                   (Section 4.2): output-stationary accumulators, weights pre-rotated so
+//                   that the accumulator of output row i is the compile-time slot i mod bh,
+//                   one output row stored per start row, epilogue for the last bh-1 rows.
+//                   Used for fp32 and as the reference GPU path for every dtype.
+//  * stripe_kernel - MFMA kernel for fp16 / bf16.  A matrix instruction produces 16 output
+//                   rows at once, so the accumulators are aligned 16-row stripes and an
+//                   unaligned block contributes to (at most) two of them through
+//                   zero-filled operand rows; the gathered X rows are staged in LDS and
+//                   read back transposed (ds_read_b64_tr_b16) straight into operand order.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdlib>
+#include <cstring>
+
+#include "ubp_internal.h"
+
+namespace ubp {
+
+namespace {
+
+typedef short short4v __attribute__((ext_vector_type(4)));
+typedef short short8v __attribute__((ext_vector_type(8)));
+typedef _Float16 half8v __attribute__((ext_vector_type(8)));
+typedef __bf16 bf8v __attribute__((ext_vector_type(8)));
+typedef float float4v __attribute__((ext_vector_type(4)));
+
+struct DeviceGuard {
+    int prev = -1;
+    bool ok = true;
+    explicit DeviceGuard(int dev) {
+        if (hipGetDevice(&prev) != hipSuccess) { ok = false; prev = -1; }
+        else if (prev != dev && hipSetDevice(dev) != hipSuccess) { ok = false; prev = -1; }
+        if (!ok) (void)hipGetLastError(); // do not leave a sticky error for the caller's next HIP call
+    }
+    ~DeviceGuard() {
+        if (prev >= 0) (void)hipSetDevice(prev);
+    }
+};
+
+template <class T>
+bool dev_copy(T **dst, const T *src, size_t n, int64_t *bytes) {
+    const size_t sz = std::max<size_t>(n, 1) * sizeof(T);
+    if (hipMalloc(reinterpret_cast<void **>(dst), sz) != hipSuccess) { *dst = nullptr; return false; }
+    *bytes += (int64_t)sz;
+    if (n && hipMemcpy(*dst, src, n * sizeof(T), hipMemcpyHostToDevice) != hipSuccess) return false;
+    return true;
+}
+
+// ------------------------------------------------------------------ element helpers
+template <typename T> __device__ __forceinline__ float to_f32(T v) { return (float)v; }
+template <typename T> __device__ __forceinline__ T from_f32(float v) { return (T)v; } // round to nearest even
+
+template <typename T, int VEC> struct VecOf { typedef T type __attribute__((ext_vector_type(VEC))); };
+template <typename T> struct VecOf<T, 1> { typedef T type; };
+
+template <typename T, int VEC>
+__device__ __forceinline__ void load_row(const T *p, float (&out)[VEC]) {
+    if constexpr (VEC == 1) {
+        out[0] = to_f32(*p);
+    } else {
+        typedef typename VecOf<T, VEC>::type V;
+        V v = *reinterpret_cast<const V *>(p);
+#pragma unroll
+        for (int t = 0; t < VEC; ++t) out[t] = to_f32((T)v[t]);
+    }
+}
+
+template <typename T, int VEC>
+__device__ __forceinline__ void store_row(T *p, const float (&in)[VEC]) {
+    if constexpr (VEC == 1) {
+        *p = from_f32<T>(in[0]);
+    } else {
+        typedef typename VecOf<T, VEC>::type V;
+        V v;
+#pragma unroll
+        for (int t = 0; t < VEC; ++t) v[t] = from_f32<T>(in[t]);
+        *reinterpret_cast<V *>(p) = v;
+    }
+}
+
+// ------------------------------------------------------------------ WROS vector kernel
+// Grid: x = column tiles of 256*VEC columns, y = ranges of `rpr` output rows.
+// A thread owns VEC columns and BH accumulator rows (slots).  Start rows are walked in
+// increasing order; the loop is unrolled by BH so that "slot = start row mod BH" is a
+// compile-time register name.  After start row i is done, output row i is complete (later
+// blocks start below it): its slot is stored and cleared, the other slots keep
+// accumulating.  A range re-walks the BH-1 start rows above it, whose blocks reach into the
+// range, and drops what those blocks add to rows it does not own.
+template <typename TX, typename TY, int BH, int VEC>
+__global__ __launch_bounds__(256) void wros_kernel(const int32_t *__restrict__ indptr, const int32_t *__restrict__ indices,
+                                                  const float *__restrict__ vals, const TX *__restrict__ X, int64_t ldx,
+                                                  TY *__restrict__ Y, int64_t ldy, int M, int N, int bw, int rpr) {
+    const int col = (blockIdx.x * 256 + threadIdx.x) * VEC;
+    if (col >= N) return;
+    const int lo = blockIdx.y * rpr;
+    const int hi = min(lo + rpr, M);
+    const int last_start = M - BH; // start rows beyond this hold no block (epilogue rows)
+    float acc[BH][VEC];
+#pragma unroll
+    for (int s = 0; s < BH; ++s)
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) acc[s][v] = 0.f;
+
+    const int first = max(0, lo - BH + 1);
+    for (int base = (first / BH) * BH; base < hi; base += BH) {
+#pragma unroll
+        for (int u = 0; u < BH; ++u) {
+            const int i = base + u; // start row; i mod BH == u
+            if (i < first || i >= hi) continue;
+            if (i <= last_start) {
+                const int b1 = indptr[i + 1];
+                for (int b = indptr[i]; b < b1; ++b) {
+                    const int c = indices[b];
+                    const float *w = vals + (int64_t)b * bw * BH;
+                    for (int q = 0; q < bw; ++q) {
+                        float x[VEC];
+                        load_row<TX, VEC>(X + (int64_t)(c + q) * ldx + col, x);
+#pragma unroll
+                        for (int s = 0; s < BH; ++s) {
+                            const float ws = w[q * BH + s];
+#pragma unroll
+                            for (int v = 0; v < VEC; ++v) acc[s][v] = fmaf(ws, x[v], acc[s][v]);
+                        }
+                    }
+                }
+            }
+            if (i >= lo) store_row<TY, VEC>(Y + (int64_t)i * ldy + col, acc[u]);
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) acc[u][v] = 0.f;
+        }
+    }
+}
+
+// ------------------------------------------------------------------ MFMA stripe kernel
+struct StripeArgs {
+    const int32_t *seg_ptr;
+    const int32_t *rg_order;
+    const uint32_t *step_meta;
+    const uint32_t *lane_rows;
+    const uint16_t *wfrag;
+    const uint16_t *X;
+    void *Y;
+    int64_t ldx, ldy;
+    int M, K, N;
+    int nrg, nch;
+    int n_coltiles, n_wgrows;
+    int vec_ok; // X and Y allow 16-byte vector access on every row
+};
+
+template <bool BF16>
+__device__ __forceinline__ float4v mfma16(short8v a, short8v b, float4v c) {
+    if constexpr (BF16)
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf8v, a), __builtin_bit_cast(bf8v, b), c, 0, 0, 0);
+    else
+        return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8v, a), __builtin_bit_cast(half8v, b), c, 0, 0, 0);
+}
+
+__device__ __forceinline__ short4v lds_read_tr(const char *lds_base, int byte_off) {
+    typedef __attribute__((address_space(3))) short4v *lds_ptr;
+    return __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(lds_base + byte_off));
+}
+
+template <bool BF16> struct Elem16 { typedef _Float16 type; };
+template <> struct Elem16<true> { typedef __bf16 type; };
+
+// One workgroup = `waves` wavefronts that share one tile of 16*CT columns of X / Y; each
+// wavefront owns one row group (G aligned 16-row stripes) and keeps its G*CT output tiles
+// in fp32 accumulators for the whole K loop (output stationary).  X is staged chunk by
+// chunk (kChunkRows rows) in LDS; a step gathers 32 staged rows with two transposed LDS
+// reads per lane and issues one 16x16x32 MFMA per (stripe with nonzero weights, column
+// tile).  The product is formed transposed (pixels x rows) so that a lane ends up holding
+// 4*CT consecutive pixels of one output row.
+template <bool BF16, typename TY, int G, int CT>
+__global__ __launch_bounds__(G * CT > 16 ? 512 : 1024) void stripe_kernel(StripeArgs a) {
+    constexpr int NTW = 16 * CT;        // columns per workgroup
+    constexpr int PITCH = NTW * 2 + 8;  // LDS row pitch in bytes (8-byte skew against bank conflicts)
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+
+    // workgroup -> (column tile, workgroup row); consecutive workgroup ids go round-robin
+    // over the 8 XCDs, so tiles are dealt by id mod 8 and all row groups of one column tile
+    // run on one XCD (they share the X tile in that XCD's L2).
+    const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
+    const int my_tiles = (a.n_coltiles - xcd + 7) >> 3;
+    if (local >= my_tiles * a.n_wgrows) return;
+    const int ctile = xcd + 8 * (local / a.n_wgrows);
+    const int wgrow = local % a.n_wgrows;
+
+    const int nthreads = blockDim.x;
+    const int waves = nthreads >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    const int col0 = ctile * NTW;
+    const int rgi = wgrow * waves + wave;
+    const int rg = rgi < a.nrg ? a.rg_order[rgi] : -1;
+
+    float4v acc[G][CT];
+#pragma unroll
+    for (int j = 0; j < G; ++j)
+#pragma unroll
+        for (int c = 0; c < CT; ++c) acc[j][c] = float4v{0.f, 0.f, 0.f, 0.f};
+
+    // lane's byte offset inside a staged row for its transposed reads: lanes 4e..4e+3 of a
+    // 16-lane group read row e; lane (t mod 4) reads pixels 4*CT*(t mod 4) + 4*ct .. +3
+    const int lane_off = (4 * CT * (lane & 3)) * 2;
+
+    for (int ch = 0; ch < a.nch; ++ch) {
+        const int k0 = ch * kChunkRows;
+        const int rows = min(kChunkRows, a.K - k0);
+        __syncthreads(); // everyone is done reading the previous chunk
+        // ---- stage X[k0 .. k0+rows) x [col0, col0+NTW) in LDS, zero beyond column N
+        constexpr int PIECES = 2 * CT; // 16-byte pieces per row
+        for (int piece = threadIdx.x; piece < rows * PIECES; piece += nthreads) {
+            const int r = piece / PIECES, seg = piece % PIECES;
+            const int c = col0 + seg * 8;
+            const uint16_t *src = a.X + (int64_t)(k0 + r) * a.ldx + c;
+            uint2 lo = {0u, 0u}, hi = {0u, 0u};
+            if (a.vec_ok && c + 8 <= a.N) {
+                const uint4 v = *reinterpret_cast<const uint4 *>(src);
+                lo = uint2{v.x, v.y};
+                hi = uint2{v.z, v.w};
+            } else {
+                uint16_t e[8];
+#pragma unroll
+                for (int t = 0; t < 8; ++t) e[t] = (c + t < a.N) ? src[t] : (uint16_t)0;
+                lo = uint2{(uint32_t)e[0] | ((uint32_t)e[1] << 16), (uint32_t)e[2] | ((uint32_t)e[3] << 16)};
+                hi = uint2{(uint32_t)e[4] | ((uint32_t)e[5] << 16), (uint32_t)e[6] | ((uint32_t)e[7] << 16)};
+            }
+            char *dst = smem + r * PITCH + seg * 16;
+            *reinterpret_cast<uint2 *>(dst) = lo;
+            *reinterpret_cast<uint2 *>(dst + 8) = hi;
+        }
+        __syncthreads();
+        if (rg < 0) continue;
+        const int s1 = a.seg_ptr[rg * a.nch + ch + 1];
+        for (int s = a.seg_ptr[rg * a.nch + ch]; s < s1; ++s) {
+            const uint32_t meta = a.step_meta[s];
+            const uint32_t lr = a.lane_rows[(int64_t)s * 64 + lane];
+            const int off_lo = (int)(lr & 0xffffu) * PITCH + lane_off;
+            const int off_hi = (int)(lr >> 16) * PITCH + lane_off;
+            short8v xf[CT];
+#pragma unroll
+            for (int c = 0; c < CT; ++c) {
+                const short4v p0 = lds_read_tr(smem, off_lo + c * 8);
+                const short4v p1 = lds_read_tr(smem, off_hi + c * 8);
+                xf[c] = __builtin_shufflevector(p0, p1, 0, 1, 2, 3, 4, 5, 6, 7);
+            }
+            const uint4 *wp = reinterpret_cast<const uint4 *>(a.wfrag) + (int64_t)(meta >> 8) * 64 + lane;
+#pragma unroll
+            for (int j = 0; j < G; ++j) {
+                if (meta & (1u << j)) {
+                    const short8v wf = __builtin_bit_cast(short8v, *wp);
+                    wp += 64;
+#pragma unroll
+                    for (int c = 0; c < CT; ++c) acc[j][c] = mfma16<BF16>(xf[c], wf, acc[j][c]);
+                }
+            }
+        }
+    }
+
+    // ---- store: lane (g = lane/16, n = lane%16) holds pixels col0 + 4*CT*g + 4*ct + v of
+    // row 16*(G*rg + j) + n.  Rows no block touches are stored as zeros like any other.
+    if (rg < 0) return;
+    const int g = lane >> 4, n = lane & 15;
+    const int px0 = col0 + 4 * CT * g;
+    if (px0 >= a.N) return;
+    TY *Yt = static_cast<TY *>(a.Y);
+#pragma unroll
+    for (int j = 0; j < G; ++j) {
+        const int row = (rg * G + j) * kStripe + n;
+        if (row >= a.M) continue;
+        TY *dst = Yt + (int64_t)row * a.ldy + px0;
+        if (a.vec_ok && px0 + 4 * CT <= a.N) {
+#pragma unroll
+            for (int c = 0; c < CT; ++c) {
+                float v[4] = {acc[j][c][0], acc[j][c][1], acc[j][c][2], acc[j][c][3]};
+                store_row<TY, 4>(dst + 4 * c, v);
+            }
+        } else {
+#pragma unroll
+            for (int c = 0; c < CT; ++c)
+#pragma unroll
+                for (int v = 0; v < 4; ++v)
+                    if (px0 + 4 * c + v < a.N) dst[4 * c + v] = from_f32<TY>(acc[j][c][v]);
+        }
+    }
+}
+
+// ------------------------------------------------------------------ launchers
+template <typename TX, typename TY, int VEC>
+ubp_status launch_wros_bh(const ubp_packed *p, const void *X, int64_t ldx, int N, void *Y, int64_t ldy, int rpr,
+                          hipStream_t st) {
+    dim3 grid((unsigned)((N + 256 * VEC - 1) / (256 * VEC)), (unsigned)((p->M + rpr - 1) / rpr));
+#define UBP_WROS_CASE(BH)                                                                                              \
+    case BH:                                                                                                           \
+        hipLaunchKernelGGL((wros_kernel<TX, TY, BH, VEC>), grid, dim3(256), 0, st, p->d_indptr, p->d_indices,         \
+                           p->d_values_f32, static_cast<const TX *>(X), ldx, static_cast<TY *>(Y), ldy, p->M, N, p->bw, \
+                           rpr);                                                                                       \
+        break;
+    switch (p->bh) {
+        UBP_WROS_CASE(1) UBP_WROS_CASE(2) UBP_WROS_CASE(3) UBP_WROS_CASE(4) UBP_WROS_CASE(5) UBP_WROS_CASE(6)
+        UBP_WROS_CASE(7) UBP_WROS_CASE(8) UBP_WROS_CASE(9) UBP_WROS_CASE(10) UBP_WROS_CASE(11) UBP_WROS_CASE(12)
+        UBP_WROS_CASE(13) UBP_WROS_CASE(14) UBP_WROS_CASE(15) UBP_WROS_CASE(16)
+    default: return UBP_ERR_UNSUPPORTED;
+    }
+#undef UBP_WROS_CASE
+    return hipGetLastError() == hipSuccess ? UBP_OK : UBP_ERR_DEVICE;
+}
+
+template <typename TX, typename TY>
+ubp_status launch_wros(const ubp_packed *p, const void *X, int64_t ldx, int N, void *Y, int64_t ldy, int rpr,
+                       hipStream_t st) {
+    // 4 columns per thread when every row of X and Y can be accessed as an aligned 4-vector
+    const bool vec = (N % 4 == 0) && (ldx % 4 == 0) && (ldy % 4 == 0) &&
+                     (reinterpret_cast<uintptr_t>(X) % (4 * sizeof(TX)) == 0) &&
+                     (reinterpret_cast<uintptr_t>(Y) % (4 * sizeof(TY)) == 0) && N >= 2048;
+    return vec ? launch_wros_bh<TX, TY, 4>(p, X, ldx, N, Y, ldy, rpr, st)
+               : launch_wros_bh<TX, TY, 1>(p, X, ldx, N, Y, ldy, rpr, st);
+}
+
+template <bool BF16, typename TY, int G, int CT>
+ubp_status launch_stripe_inst(const StripeArgs &a, int waves, hipStream_t st) {
+    constexpr int PITCH = 16 * CT * 2 + 8;
+    const size_t lds = (size_t)kChunkRows * PITCH;
+    static bool attr_set = false; // per instantiation; raising the limit is idempotent
+    if (!attr_set) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&stripe_kernel<BF16, TY, G, CT>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+            return UBP_ERR_DEVICE;
+        attr_set = true;
+    }
+    const unsigned grid = 8u * (unsigned)((a.n_coltiles + 7) / 8) * (unsigned)a.n_wgrows;
+    hipLaunchKernelGGL((stripe_kernel<BF16, TY, G, CT>), dim3(grid), dim3((unsigned)waves * 64), lds, st, a);
+    return hipGetLastError() == hipSuccess ? UBP_OK : UBP_ERR_DEVICE;
+}
+
+template <bool BF16, typename TY>
+ubp_status launch_stripe(const StripeArgs &a, int G, int CT, int waves, hipStream_t st) {
+    if (G * CT > 16 && waves > 8) return UBP_ERR_UNSUPPORTED;
+#define UBP_SG_CASE(GG, CC) \
+    if (G == GG && CT == CC) return launch_stripe_inst<BF16, TY, GG, CC>(a, waves, st);
+    UBP_SG_CASE(1, 4) UBP_SG_CASE(2, 4) UBP_SG_CASE(4, 4) UBP_SG_CASE(1, 8) UBP_SG_CASE(2, 8) UBP_SG_CASE(4, 8)
+#undef UBP_SG_CASE
+    return UBP_ERR_UNSUPPORTED;
+}
+
+int env_int(const char *name, int dflt) {
+    const char *v = std::getenv(name);
+    return v && *v ? std::atoi(v) : dflt;
+}
+
+} // namespace
+
+// ------------------------------------------------------------------ upload / release
+ubp_status upload(ubp_packed *p) {
+    int count = 0;
+    if (hipGetDeviceCount(&count) != hipSuccess || p->device >= count) {
+        (void)hipGetLastError();
+        p->device = UBP_HOST_ONLY; // nothing was allocated; nothing to release
+        return UBP_ERR_DEVICE;
+    }
+    DeviceGuard guard(p->device);
+    if (!guard.ok) {
+        p->device = UBP_HOST_ONLY;
+        return UBP_ERR_DEVICE;
+    }
+    bool ok = true;
+    ok = ok && dev_copy(&p->d_indptr, p->indptr.data(), p->indptr.size(), &p->device_bytes);
+    ok = ok && dev_copy(&p->d_indices, p->indices.data(), p->indices.size(), &p->device_bytes);
+    {
+        // rotated values widened to fp32 (exact for fp16 and bf16) for the vector kernel
+        const int64_t n = p->nb * p->bw * p->bh;
+        std::vector<float> f((size_t)n);
+        if (p->dtype == UBP_F32) {
+            if (n) std::memcpy(f.data(), p->values.data(), (size_t)n * 4);
+        } else {
+            const uint16_t *h = reinterpret_cast<const uint16_t *>(p->values.data());
+            for (int64_t t = 0; t < n; ++t) {
+                if (p->dtype == UBP_BF16) {
+                    const uint32_t u = (uint32_t)h[t] << 16;
+                    std::memcpy(&f[(size_t)t], &u, 4);
+                } else {
+                    _Float16 hv;
+                    std::memcpy(&hv, &h[t], 2);
+                    f[(size_t)t] = (float)hv;
+                }
+            }
+        }
+        ok = ok && dev_copy(&p->d_values_f32, f.data(), f.size(), &p->device_bytes);
+    }
+    if (p->dtype != UBP_F32) {
+        for (int s = 0; s < kNumG && ok; ++s) {
+            const StripeLayout &L = p->sg[s];
+            StripeLayoutDev &D = p->d_sg[s];
+            ok = ok && dev_copy(&D.seg_ptr, L.seg_ptr.data(), L.seg_ptr.size(), &p->device_bytes);
+            ok = ok && dev_copy(&D.rg_order, L.rg_order.data(), L.rg_order.size(), &p->device_bytes);
+            ok = ok && dev_copy(&D.step_meta, L.step_meta.data(), L.step_meta.size(), &p->device_bytes);
+            ok = ok && dev_copy(&D.lane_rows, L.lane_rows.data(), L.lane_rows.size(), &p->device_bytes);
+            ok = ok && dev_copy(&D.wfrag, L.wfrag.data(), L.wfrag.size(), &p->device_bytes);
+        }
+    }
+    if (!ok) {
+        (void)hipGetLastError();
+        return UBP_ERR_ALLOC;
+    }
+    return UBP_OK;
+}
+
+void release_device(ubp_packed *p) {
+    if (!p || p->device == UBP_HOST_ONLY) return;
+    DeviceGuard guard(p->device);
+    if (!guard.ok) return;
+    auto rel = [](auto *&ptr) {
+        if (ptr) (void)hipFree(ptr);
+        ptr = nullptr;
+    };
+    rel(p->d_indptr);
+    rel(p->d_indices);
+    rel(p->d_values_f32);
+    for (int s = 0; s < kNumG; ++s) {
+        rel(p->d_sg[s].seg_ptr);
+        rel(p->d_sg[s].rg_order);
+        rel(p->d_sg[s].step_meta);
+        rel(p->d_sg[s].lane_rows);
+        rel(p->d_sg[s].wfrag);
+    }
+}
+
+} // namespace ubp
+
+// ------------------------------------------------------------------ C ABI
+extern "C" {
+
+ubp_status ubp_spmm_plan(const ubp_packed *p, const void *X_dev, int64_t ldx, int32_t N, void *Y_dev, int64_t ldy,
+                         ubp_dtype y_dtype, void *hip_stream, const ubp_plan *plan) {
+    using namespace ubp;
+    if (!p || N < 0) return UBP_ERR_INVALID_ARG;
+    if (p->device == UBP_HOST_ONLY) return UBP_ERR_INVALID_ARG;
+    if (y_dtype != UBP_F32 && y_dtype != p->dtype) return UBP_ERR_INVALID_ARG;
+    if (N == 0) return UBP_OK;
+    if (!X_dev || !Y_dev || ldx < N || ldy < N) return UBP_ERR_INVALID_ARG;
+    ubp_plan pl;
+    std::memset(&pl, 0, sizeof pl);
+    if (plan) pl = *plan;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    DeviceGuard guard(p->device);
+    if (!guard.ok) return UBP_ERR_DEVICE;
+
+    int kernel = pl.kernel;
+    if (kernel == 0) kernel = env_int("UBP_KERNEL", 0);
+    if (kernel == 0) kernel = (p->dtype == UBP_F32) ? 1 : 2;
+    if (kernel == 2 && p->dtype == UBP_F32) return UBP_ERR_UNSUPPORTED;
+    if (kernel != 1 && kernel != 2) return UBP_ERR_INVALID_ARG;
+
+    if (kernel == 1) {
+        if (p->bh > 16) return UBP_ERR_UNSUPPORTED;
+        int rpr = pl.rows_per_range;
+        if (rpr == 0) {
+            // enough row ranges to fill the chip, but each at least 4 block heights tall so
+            // that re-walking bh-1 start rows stays a small fraction of the work
+            const int coltiles = (N + 255) / 256;
+            int ranges = std::max(1, 2048 / std::max(1, coltiles));
+            rpr = std::max(4 * p->bh, (p->M + ranges - 1) / ranges);
+            rpr = ((rpr + p->bh - 1) / p->bh) * p->bh;
+        }
+        if (rpr < 1) return UBP_ERR_INVALID_ARG;
+        if ((p->M + rpr - 1) / rpr > 65535) rpr = (p->M + 65534) / 65535; // grid.y limit
+        switch (p->dtype) {
+        case UBP_F32: return launch_wros<float, float>(p, X_dev, ldx, N, Y_dev, ldy, rpr, st);
+        case UBP_F16:
+            return y_dtype == UBP_F32 ? launch_wros<_Float16, float>(p, X_dev, ldx, N, Y_dev, ldy, rpr, st)
+                                      : launch_wros<_Float16, _Float16>(p, X_dev, ldx, N, Y_dev, ldy, rpr, st);
+        case UBP_BF16:
+            return y_dtype == UBP_F32 ? launch_wros<__bf16, float>(p, X_dev, ldx, N, Y_dev, ldy, rpr, st)
+                                      : launch_wros<__bf16, __bf16>(p, X_dev, ldx, N, Y_dev, ldy, rpr, st);
+        }
+        return UBP_ERR_INVALID_ARG;
+    }
+
+    // ---- MFMA stripe kernel
+    int CT = pl.col_tiles ? pl.col_tiles : env_int("UBP_CT", 0);
+    int G = pl.sub_stripes ? pl.sub_stripes : env_int("UBP_G", 0);
+    int waves = pl.waves ? pl.waves : env_int("UBP_WAVES", 0);
+    if (CT == 0) CT = 4;
+    if (G == 0) {
+        // largest row group that still leaves about two wavefront tiles per SIMD
+        const int64_t coltiles = (N + 16 * CT - 1) / (16 * CT);
+        G = 4;
+        while (G > 1 && ((p->M + 16 * G - 1) / (16 * G)) * coltiles < 2048) G >>= 1;
+    }
+    if (G != 1 && G != 2 && G != 4) return UBP_ERR_UNSUPPORTED;
+    if (CT != 4 && CT != 8) return UBP_ERR_UNSUPPORTED;
+    const int slot = G == 1 ? 0 : (G == 2 ? 1 : 2);
+    const StripeLayout &L = p->sg[slot];
+    const int max_waves = (G * CT > 16) ? 8 : 16;
+    if (waves == 0) waves = std::min(max_waves, std::max(1, L.nrg));
+    if (waves < 1 || waves > max_waves) return UBP_ERR_UNSUPPORTED;
+
+    StripeArgs a;
+    a.seg_ptr = p->d_sg[slot].seg_ptr;
+    a.rg_order = p->d_sg[slot].rg_order;
+    a.step_meta = p->d_sg[slot].step_meta;
+    a.lane_rows = p->d_sg[slot].lane_rows;
+    a.wfrag = p->d_sg[slot].wfrag;
+    a.X = static_cast<const uint16_t *>(X_dev);
+    a.Y = Y_dev;
+    a.ldx = ldx;
+    a.ldy = ldy;
+    a.M = p->M;
+    a.K = p->K;
+    a.N = N;
+    a.nrg = L.nrg;
+    a.nch = L.nch;
+    a.n_coltiles = (N + 16 * CT - 1) / (16 * CT);
+    a.n_wgrows = (L.nrg + waves - 1) / waves;
+    const size_t ysz = (y_dtype == UBP_F32) ? 4 : 2;
+    a.vec_ok = (ldx % 8 == 0) && (reinterpret_cast<uintptr_t>(X_dev) % 16 == 0) && ((ldy * ysz) % 16 == 0) &&
+               (reinterpret_cast<uintptr_t>(Y_dev) % 16 == 0);
+    if (p->dtype == UBP_BF16)
+        return y_dtype == UBP_F32 ? launch_stripe<true, float>(a, G, CT, waves, st)
+                                  : launch_stripe<true, __bf16>(a, G, CT, waves, st);
+    return y_dtype == UBP_F32 ? launch_stripe<false, float>(a, G, CT, waves, st)
+                              : launch_stripe<false, _Float16>(a, G, CT, waves, st);
+}
+
+ubp_status ubp_spmm(const ubp_packed *p, const void *X_dev, int64_t ldx, int32_t N, void *Y_dev, int64_t ldy,
+                    ubp_dtype y_dtype, void *hip_stream) {
+    return ubp_spmm_plan(p, X_dev, ldx, N, Y_dev, ldy, y_dtype, hip_stream, nullptr);
+}
+
+} // extern "C"

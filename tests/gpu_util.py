@@ -1,0 +1,85 @@
+"""Helpers for the GPU parity tests: device buffers through torch, calls through the C ABI."""
+import numpy as np
+import torch
+
+import paper_2407_19644_amd as ubp
+from synthetic import decode_f64
+
+_TORCH = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}
+
+
+def to_device(enc, dtype):
+    t = torch.from_numpy(np.ascontiguousarray(enc))
+    if dtype == "bf16":
+        t = t.view(torch.bfloat16)
+    return t.cuda()
+
+
+def from_device(t, dtype):
+    """Exact float64 values of a device tensor."""
+    t = t.detach().cpu()
+    if dtype == "bf16":
+        return decode_f64(t.view(torch.uint16).numpy(), "bf16")
+    return t.numpy().astype(np.float64)
+
+
+def run_spmm(W_enc, dtype, bh, bw, blocks, X_enc, y_dtype=None, plan=None, ldx=None, ldy=None, packed=None,
+             prefill=float("nan")):
+    """Y (float64 numpy, exact) computed by the HIP path; Y is pre-filled with NaN."""
+    y_dtype = y_dtype or dtype
+    M = W_enc.shape[0]
+    K, N = X_enc.shape
+    own = packed is None
+    if own:
+        packed = ubp.pack(W_enc, dtype, bh, bw, blocks, device=torch.cuda.current_device())
+    ldx = ldx or N
+    ldy = ldy or N
+    Xd = torch.zeros((K, ldx), dtype=_TORCH[dtype], device="cuda")
+    Xd[:, :N] = to_device(X_enc, dtype)
+    Yd = torch.full((M, ldy), prefill, dtype=_TORCH[y_dtype], device="cuda")
+    stream = torch.cuda.current_stream().cuda_stream
+    ubp.spmm(packed, Xd.data_ptr(), ldx, N, Yd.data_ptr(), ldy, y_dtype, stream, plan)
+    torch.cuda.synchronize()
+    out = from_device(Yd, y_dtype)
+    if own:
+        packed.free()
+    if ldy > N:
+        pad = out[:, N:]
+        assert np.isnan(pad).all() if np.isnan(prefill) else (pad == prefill).all(), "wrote beyond column N"
+    return out[:, :N]
+
+
+_MANT = {"f16": (10, -24), "bf16": (7, -133)}
+
+
+def half_ulp(v, y_dtype):
+    """Half the spacing of the 16-bit output format at |v| (element-wise)."""
+    mant, emin = _MANT[y_dtype]
+    a = np.maximum(np.abs(v), 2.0 ** (emin + mant))
+    return 0.5 * np.maximum(2.0 ** (np.floor(np.log2(a)) - mant), 2.0 ** emin)
+
+
+def check(Y, Yref, Yabs, dtype, y_dtype=None):
+    """The parity bar.
+    fp32 layer: max|dY| <= 1e-5 max|Y| and, componentwise, |dY| <= 1e-5 (|W||X|).
+    fp16 / bf16 inputs with fp32 accumulation, Y read back in fp32: max|dY| <= 2e-3 max|Y|.
+    Y stored in the 16-bit input type: the fp32 accumulator is rounded to nearest once, so
+    |dY| <= half an output ulp at |Y_ref| (+1%) plus 1e-4 max|Y| for the accumulation; for
+    fp16 that is inside 2e-3 max|Y| as well, for bf16 half an ulp alone reaches 2^-8 |Y|,
+    so the 2e-3 bar is not attainable by any implementation and is not applied."""
+    y_dtype = y_dtype or dtype
+    assert Y.shape == Yref.shape
+    assert np.isfinite(Y).all(), "NaN/Inf left in Y: %d elements not written" % int((~np.isfinite(Y)).sum())
+    scale = np.abs(Yref).max()
+    err = np.abs(Y - Yref)
+    if dtype == "f32":
+        assert err.max() <= 1e-5 * scale + 1e-30, (err.max(), scale)
+        if Yabs is not None:
+            assert (err <= 1e-5 * Yabs + 1e-30).all(), float((err / (Yabs + 1e-300)).max())
+    elif y_dtype == "f32":
+        assert err.max() <= 2e-3 * scale + 1e-30, (err.max() / (scale + 1e-300), scale)
+    else:
+        bound = 1.01 * half_ulp(Yref, y_dtype) + 1e-4 * scale
+        assert (err <= bound).all(), (float((err / bound).max()), scale)
+        if y_dtype == "f16":
+            assert err.max() <= 2e-3 * scale + 1e-30

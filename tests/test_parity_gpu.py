@@ -1,0 +1,204 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle, element by
+element on the same seeded inputs."""
+import itertools
+
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+
+import oracle                                    # noqa: E402
+import paper_2407_19644_amd as ubp               # noqa: E402
+from synthetic import (CONFIGS, decode_f64, encode, get_config, make_activations, make_layer,   # noqa: E402
+                       make_weights, select_blocks)
+from gpu_util import check, run_spmm             # noqa: E402
+
+pytestmark = pytest.mark.gpu
+
+
+def _plan(**kw):
+    p = ubp.Plan()
+    for k, v in kw.items():
+        setattr(p, k, v)
+    return p
+
+
+def _layer(M, K, N, bh, bw, density, dtype, seed, x_dist="normal", mode="uniform"):
+    blocks = select_blocks(M, K, bh, bw, density, seed, mode, 1.1)
+    W = make_weights(M, K, seed + 1, dtype)
+    X = make_activations(K, N, seed + 2, dtype, x_dist)
+    return blocks, W, X
+
+
+def _oracle(W, dtype, bh, bw, blocks, X, rows=None):
+    return oracle.spmm(decode_f64(W, dtype), bh, bw, blocks, decode_f64(X, dtype), rows=rows, want_abs=True)
+
+
+# ------------------------------------------------------------------ small shapes, every kernel
+SMALL = [  # M, K, N, bh, bw, density: several tiles, ragged tails, odd pitches
+    (64, 64, 196, 4, 4, 0.5),
+    (70, 45, 67, 3, 1, 0.4),
+    (100, 300, 333, 8, 8, 0.2),
+    (130, 600, 1000, 16, 16, 0.15),
+    (33, 40, 129, 5, 3, 0.3),
+    (48, 520, 72, 2, 6, 0.35),
+    (16, 16, 16, 16, 16, 1.0),
+    (257, 31, 40, 1, 1, 0.3),
+]
+
+
+@pytest.mark.parametrize("shape", SMALL, ids=lambda s: "x".join(map(str, s)))
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
+def test_wros_kernel_small(shape, dtype):
+    M, K, N, bh, bw, d = shape
+    blocks, W, X = _layer(M, K, N, bh, bw, d, dtype, seed=M + K)
+    Yref, Yabs = _oracle(W, dtype, bh, bw, blocks, X)
+    for y_dtype in {dtype, "f32"}:
+        for rpr in (0, bh, 3 * bh):
+            Y = run_spmm(W, dtype, bh, bw, blocks, X, y_dtype, _plan(kernel=1, rows_per_range=rpr))
+            check(Y, Yref, Yabs, dtype, y_dtype)
+
+
+@pytest.mark.parametrize("shape", SMALL + [(90, 64, 50, 20, 3, 0.25)], ids=lambda s: "x".join(map(str, s)))
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+def test_stripe_kernel_small(shape, dtype):
+    M, K, N, bh, bw, d = shape
+    blocks, W, X = _layer(M, K, N, bh, bw, d, dtype, seed=M + K + 1)
+    Yref, Yabs = _oracle(W, dtype, bh, bw, blocks, X)
+    for G, CT in itertools.product((1, 2, 4), (4, 8)):
+        for y_dtype in (dtype, "f32"):
+            Y = run_spmm(W, dtype, bh, bw, blocks, X, y_dtype, _plan(kernel=2, sub_stripes=G, col_tiles=CT))
+            check(Y, Yref, Yabs, dtype, y_dtype)
+    Y = run_spmm(W, dtype, bh, bw, blocks, X, dtype, _plan(kernel=2, sub_stripes=1, col_tiles=4, waves=3))
+    check(Y, Yref, Yabs, dtype)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
+def test_unaligned_pitches_and_pointers(dtype):
+    """Leading dimensions that are not multiples of the vector width take the element-wise
+    path; nothing may be written beyond column N."""
+    M, K, N, bh, bw = 50, 70, 101, 4, 4
+    blocks, W, X = _layer(M, K, N, bh, bw, 0.3, dtype, seed=9)
+    Yref, Yabs = _oracle(W, dtype, bh, bw, blocks, X)
+    for ldx, ldy in [(N, N), (N + 3, N + 5), (104, 112)]:
+        Y = run_spmm(W, dtype, bh, bw, blocks, X, dtype, None, ldx=ldx, ldy=ldy)
+        check(Y, Yref, Yabs, dtype)
+        Y = run_spmm(W, dtype, bh, bw, blocks, X, dtype, _plan(kernel=1), ldx=ldx, ldy=ldy)
+        check(Y, Yref, Yabs, dtype)
+
+
+# ------------------------------------------------------------------ exact special cases
+@pytest.mark.parametrize("dtype,kernel", [("f32", 1), ("f16", 1), ("bf16", 1), ("f16", 2), ("bf16", 2)])
+def test_identity_x_returns_densified_w_bit_exactly(dtype, kernel):
+    M, K, bh, bw = 90, 128, 4, 4
+    blocks = select_blocks(M, K, bh, bw, 0.3, seed=3)
+    W = make_weights(M, K, 4, dtype)
+    X = encode(np.eye(K, dtype=np.float32), dtype)
+    Wd = oracle.densify(decode_f64(W, dtype), bh, bw, blocks)
+    Y = run_spmm(W, dtype, bh, bw, blocks, X, dtype, _plan(kernel=kernel))
+    assert np.array_equal(Y, Wd)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_empty_block_list_and_untouched_rows_are_zero(dtype):
+    M, K, N = 40, 32, 70
+    X = make_activations(K, N, 1, dtype, "normal")
+    W = make_weights(M, K, 2, dtype)
+    Y = run_spmm(W, dtype, 4, 4, np.zeros((0, 2), np.int32), X)
+    assert np.array_equal(Y, np.zeros((M, N))) and not np.signbit(Y).any()
+    Y = run_spmm(W, dtype, 4, 4, [(17, 5)], X)          # rows 0..16 and 21..39 have no block
+    Yref, Yabs = _oracle(W, dtype, 4, 4, [(17, 5)], X)
+    check(Y, Yref, Yabs, dtype)
+    assert (Y[:17] == 0).all() and (Y[21:] == 0).all()
+
+
+def test_aligned_origins_match_oracle():
+    """Aligned block pruning is the special case with origins on multiples of the block size."""
+    M, K, N, bh, bw = 64, 96, 200, 8, 8
+    rng = np.random.default_rng(0)
+    cells = [(i * bh, j * bw) for i in range(M // bh) for j in range(K // bw)]
+    blocks = [cells[t] for t in rng.permutation(len(cells))[:30]]
+    for dtype in ("f32", "f16"):
+        W = make_weights(M, K, 5, dtype)
+        X = make_activations(K, N, 6, dtype, "normal")
+        Yref, Yabs = _oracle(W, dtype, bh, bw, blocks, X)
+        check(run_spmm(W, dtype, bh, bw, blocks, X), Yref, Yabs, dtype)
+
+
+def test_all_blocks_kept_is_dense_gemm():
+    M, K, N, bh, bw = 64, 64, 150, 16, 16
+    blocks = [(r, c) for r in range(0, M, bh) for c in range(0, K, bw)]
+    for dtype in ("f32", "bf16"):
+        W = make_weights(M, K, 7, dtype)
+        X = make_activations(K, N, 8, dtype, "normal")
+        Yref = decode_f64(W, dtype) @ decode_f64(X, dtype)
+        check(run_spmm(W, dtype, bh, bw, blocks, X, "f32"), Yref, None, dtype, "f32")
+
+
+def test_two_runs_are_bit_identical_and_columns_commute():
+    cfg = get_config("c1")
+    blocks, W, X = make_layer(cfg, N=400)
+    Y1 = run_spmm(W, cfg.dtype, cfg.bh, cfg.bw, blocks, X)
+    Y2 = run_spmm(W, cfg.dtype, cfg.bh, cfg.bw, blocks, X)
+    assert np.array_equal(Y1, Y2)
+    perm = np.random.default_rng(0).permutation(400)
+    Y3 = run_spmm(W, cfg.dtype, cfg.bh, cfg.bw, blocks, np.ascontiguousarray(X[:, perm]))
+    assert np.array_equal(Y3, Y1[:, perm])
+
+
+def test_device_errors_and_noop():
+    cfg = get_config("c0")
+    blocks, W, X = make_layer(cfg)
+    p = ubp.pack(W, "f32", cfg.bh, cfg.bw, blocks, device=0)
+    L = ubp.load_library()
+    Xd = torch.zeros(64, 196, device="cuda")
+    Yd = torch.full((64, 196), 7.0, device="cuda")
+    h = p.handle
+    assert L.ubp_spmm(h, Xd.data_ptr(), 196, 0, Yd.data_ptr(), 196, 0, None) == 0       # N = 0: no-op
+    assert L.ubp_spmm(h, Xd.data_ptr(), 100, 196, Yd.data_ptr(), 196, 0, None) == 1     # ldx < N
+    assert L.ubp_spmm(h, Xd.data_ptr(), 196, 196, Yd.data_ptr(), 196, 1, None) == 1     # y dtype mismatch
+    assert L.ubp_spmm(h, None, 196, 196, Yd.data_ptr(), 196, 0, None) == 1
+    assert L.ubp_spmm_plan(h, Xd.data_ptr(), 196, 196, Yd.data_ptr(), 196, 0, None, _plan(kernel=2)) == 4
+    torch.cuda.synchronize()
+    assert (Yd == 7.0).all()                                                           # nothing written on error
+    assert p.info(6) == 0 and p.info(8) > 0
+    p.free()
+    with pytest.raises(ubp.UBPError) as e:
+        ubp.pack(W, "f32", cfg.bh, cfg.bw, blocks, device=99)
+    assert e.value.code == 7
+
+
+# ------------------------------------------------------------------ the five layers at full size
+@pytest.mark.parametrize("name", ["c0", "c1", "c2"])
+def test_layer_full_oracle(name):
+    cfg = get_config(name)
+    blocks, W, X = make_layer(cfg)
+    Yref, Yabs = _oracle(W, cfg.dtype, cfg.bh, cfg.bw, blocks, X)
+    for y_dtype in {cfg.dtype, "f32"}:
+        Y = run_spmm(W, cfg.dtype, cfg.bh, cfg.bw, blocks, X, y_dtype)
+        check(Y, Yref, Yabs, cfg.dtype, y_dtype)
+    if cfg.dtype != "f32":
+        Y = run_spmm(W, cfg.dtype, cfg.bh, cfg.bw, blocks, X, cfg.dtype, _plan(kernel=1))
+        check(Y, Yref, Yabs, cfg.dtype)
+
+
+@pytest.mark.parametrize("name", ["c3", "c4"])
+def test_layer_full_size_sampled_rows(name):
+    """At full size the oracle computes a sample of output rows (all columns of each): the
+    first and last rows, rows around stripe boundaries, and a seeded random draw; max|Y| of
+    the sample scales the tolerance.  Every other element is checked to be finite and
+    consistent between the two kernels."""
+    cfg = get_config(name)
+    blocks, W, X = make_layer(cfg)
+    rng = np.random.default_rng(42)
+    rows = sorted(set([0, 1, 15, 16, 17, 31, 32, cfg.M - 17, cfg.M - 16, cfg.M - 1]) |
+                  set(int(r) for r in rng.integers(0, cfg.M, size=22)))
+    Yref, Yabs = _oracle(W, cfg.dtype, cfg.bh, cfg.bw, blocks, X, rows=rows)
+    Y = run_spmm(W, cfg.dtype, cfg.bh, cfg.bw, blocks, X, cfg.dtype)
+    check(Y[rows], Yref, Yabs, cfg.dtype)
+    Y32 = run_spmm(W, cfg.dtype, cfg.bh, cfg.bw, blocks, X, "f32")
+    check(Y32[rows], Yref, Yabs, cfg.dtype, "f32")
+    # the two kernels accumulate in different orders; both in fp32
+    Yv = run_spmm(W, cfg.dtype, cfg.bh, cfg.bw, blocks, X, "f32", _plan(kernel=1))
+    check(Yv[rows], Yref, Yabs, cfg.dtype, "f32")
+    assert np.abs(Yv - Y32).max() <= 1e-4 * np.abs(Yref).max()
