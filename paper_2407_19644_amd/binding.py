@@ -29,7 +29,8 @@ class UBPError(RuntimeError):
 class Plan(ctypes.Structure):
     """Mirror of ubp_plan; zero fields mean 'choose automatically'."""
     _fields_ = [("kernel", ctypes.c_int32), ("sub_stripes", ctypes.c_int32), ("col_tiles", ctypes.c_int32),
-                ("waves", ctypes.c_int32), ("rows_per_range", ctypes.c_int32), ("reserved", ctypes.c_int32 * 3)]
+                ("waves", ctypes.c_int32), ("rows_per_range", ctypes.c_int32), ("chunk_rows", ctypes.c_int32),
+                ("reserved", ctypes.c_int32 * 2)]
 
 
 _lib = None

@@ -267,10 +267,10 @@ int64_t ubp_packed_info(const ubp_packed *p, int32_t what) {
     case 6: return p->device;
     case 7: return (int64_t)p->values.size() + (int64_t)(p->indptr.size() + p->indices.size()) * 4;
     case 8: return p->device_bytes;
-    case 10: return p->sg[0].total_mfma;
-    case 11: return p->sg[1].total_mfma;
-    case 12: return p->sg[2].total_mfma;
-    default: return -1;
+    default:
+        // 100 + layout slot: weight fragments (MFMA issues per 16-column tile) of that layout
+        if (what >= 100 && what < 100 + ubp::kNumLayouts) return p->sg[what - 100].total_mfma;
+        return -1;
     }
 }
 
@@ -309,10 +309,11 @@ struct Entry {
 
 } // namespace
 
-static void build_one(ubp_packed *p, StripeLayout &L, int G) {
+static void build_one(ubp_packed *p, StripeLayout &L, int G, int kChunkRows) {
     const int M = p->M, K = p->K, bh = p->bh, bw = p->bw;
     const int rgh = kStripe * G;
     L.G = G;
+    L.chunk_rows = kChunkRows;
     L.nrg = (M + rgh - 1) / rgh;
     L.nch = (K + kChunkRows - 1) / kChunkRows;
     L.seg_ptr.assign((size_t)L.nrg * L.nch + 1, 0);
@@ -353,7 +354,7 @@ static void build_one(ubp_packed *p, StripeLayout &L, int G) {
             }
         }
         for (const Entry &e : entries) colslot[(size_t)e.k] = -1;
-        std::sort(entries.begin(), entries.end(), [](const Entry &a, const Entry &b) {
+        std::sort(entries.begin(), entries.end(), [kChunkRows](const Entry &a, const Entry &b) {
             const int ca = a.k / kChunkRows, cb = b.k / kChunkRows;
             if (ca != cb) return ca < cb;
             if (a.mask != b.mask) return a.mask < b.mask;
@@ -408,7 +409,7 @@ static void build_one(ubp_packed *p, StripeLayout &L, int G) {
 }
 
 void build_stripe_layouts(ubp_packed *p) {
-    for (int s = 0; s < kNumG; ++s) build_one(p, p->sg[s], g_of_slot(s));
+    for (int s = 0; s < kNumLayouts; ++s) build_one(p, p->sg[s], slot_G(s), slot_KC(s));
 }
 
 } // namespace ubp

@@ -10,10 +10,18 @@ namespace ubp {
 
 constexpr int kStripe = 16;     // rows of one MFMA output tile (aligned row stripe)
 constexpr int kStep = 32;       // gathered X rows consumed by one 16x16x32 MFMA
-constexpr int kChunkRows = 256; // X rows staged in LDS per chunk
-constexpr int kNumG = 3;        // layouts are built for 1, 2 and 4 stripes per wavefront
+constexpr int kNumG = 3;        // stripes per wavefront: 1, 2, 4
+constexpr int kNumKC = 4;       // X rows staged in LDS per chunk: 128, 256, 512, 1024
+constexpr int kNumLayouts = kNumG * kNumKC;
 
-inline int g_of_slot(int slot) { return 1 << slot; }
+// A layout is built for every (G, chunk rows) pair the launcher can choose.
+inline int layout_slot(int G, int KC) {
+    const int gi = G == 1 ? 0 : G == 2 ? 1 : G == 4 ? 2 : -1;
+    const int ki = KC == 128 ? 0 : KC == 256 ? 1 : KC == 512 ? 2 : KC == 1024 ? 3 : -1;
+    return (gi < 0 || ki < 0) ? -1 : gi * kNumKC + ki;
+}
+inline int slot_G(int slot) { return 1 << (slot / kNumKC); }
+inline int slot_KC(int slot) { return 128 << (slot % kNumKC); }
 
 // Host image of the MFMA kernel's private re-layout of the packed weights, for one
 // choice of G (16-row stripes handled together by one wavefront).
@@ -21,10 +29,11 @@ inline int g_of_slot(int slot) { return 1 << slot; }
 // Rows are cut into row groups of 16*G aligned rows.  For a row group the columns of W
 // that hold at least one kept weight in it are its "entries"; an entry is one row of X
 // to gather plus the 16*G weights of that column (zero where no block covers the row).
-// Entries are cut by chunk of kChunkRows X rows, ordered inside a chunk by the set of
+// Entries are cut by chunk of chunk_rows X rows, ordered inside a chunk by the set of
 // stripes they touch and then by column, and grouped 32 at a time into "steps".
 struct StripeLayout {
     int G = 0;
+    int chunk_rows = 0; // X rows per LDS chunk
     int nrg = 0;     // row groups
     int nch = 0;     // chunks of X rows
     std::vector<int32_t> seg_ptr;    // [nrg*nch + 1] first step of (row group, chunk)
@@ -54,12 +63,12 @@ struct ubp_packed {
     std::vector<int32_t> indptr, indices;
     std::vector<uint8_t> values; // nb*bw*bh elements of dtype, rotated
     // private layouts
-    ubp::StripeLayout sg[ubp::kNumG];
+    ubp::StripeLayout sg[ubp::kNumLayouts];
     // device side
     int32_t *d_indptr = nullptr;
     int32_t *d_indices = nullptr;
     float *d_values_f32 = nullptr; // rotated values widened to fp32 (exact)
-    ubp::StripeLayoutDev d_sg[ubp::kNumG];
+    ubp::StripeLayoutDev d_sg[ubp::kNumLayouts];
     int64_t device_bytes = 0;
 };
 

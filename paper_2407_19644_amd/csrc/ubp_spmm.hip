@@ -147,7 +147,7 @@ struct StripeArgs {
     void *Y;
     int64_t ldx, ldy;
     int M, K, N;
-    int nrg, nch;
+    int nrg, nch, kc; // row groups, chunks, X rows per chunk
     int n_coltiles, n_wgrows;
     int vec_ok; // X and Y allow 16-byte vector access on every row
 };
@@ -165,21 +165,28 @@ __device__ __forceinline__ short4v lds_read_tr(const char *lds_base, int byte_of
     return __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(lds_base + byte_off));
 }
 
-template <bool BF16> struct Elem16 { typedef _Float16 type; };
-template <> struct Elem16<true> { typedef __bf16 type; };
+// LDS layout of a staged chunk: row pitch = 32*CT bytes (no padding), and the 32-byte unit
+// u (16 pixels) of row r is stored at unit position u ^ swz(r), chosen so that 4
+// consecutive rows put the same logical unit on the 4 different 32-byte bank groups.
+template <int CT> __device__ __forceinline__ int swz(int row) {
+    if constexpr (CT == 2) return (row >> 1) & 1;
+    else return row & 3;
+}
 
 // One workgroup = `waves` wavefronts that share one tile of 16*CT columns of X / Y; each
 // wavefront owns one row group (G aligned 16-row stripes) and keeps its G*CT output tiles
 // in fp32 accumulators for the whole K loop (output stationary).  X is staged chunk by
-// chunk (kChunkRows rows) in LDS; a step gathers 32 staged rows with two transposed LDS
-// reads per lane and issues one 16x16x32 MFMA per (stripe with nonzero weights, column
-// tile).  The product is formed transposed (pixels x rows) so that a lane ends up holding
-// 4*CT consecutive pixels of one output row.
+// chunk in a double-buffered LDS region with direct global->LDS loads issued one chunk
+// ahead; a step gathers 32 staged rows with two transposed LDS reads per lane and column
+// tile and issues one 16x16x32 MFMA per (stripe with nonzero weights, column tile).  The
+// product is formed transposed (pixels x rows) so that a lane holds 4 consecutive pixels
+// of one output row.  Step metadata and weight fragments are fetched one step ahead.
 template <bool BF16, typename TY, int G, int CT>
 __global__ __launch_bounds__(G * CT > 16 ? 512 : 1024) void stripe_kernel(StripeArgs a) {
-    constexpr int NTW = 16 * CT;        // columns per workgroup
-    constexpr int PITCH = NTW * 2 + 8;  // LDS row pitch in bytes (8-byte skew against bank conflicts)
-    extern __shared__ __attribute__((aligned(16))) char smem[];
+    constexpr int NTW = 16 * CT;  // columns per workgroup
+    constexpr int PITCH = NTW * 2; // bytes per staged row
+    constexpr int PIECES = 2 * CT; // 16-byte pieces per staged row
+    extern __shared__ __attribute__((aligned(1024))) char smem[];
 
     // workgroup -> (column tile, workgroup row); consecutive workgroup ids go round-robin
     // over the 8 XCDs, so tiles are dealt by id mod 8 and all row groups of one column tile
@@ -197,6 +204,10 @@ __global__ __launch_bounds__(G * CT > 16 ? 512 : 1024) void stripe_kernel(Stripe
     const int col0 = ctile * NTW;
     const int rgi = wgrow * waves + wave;
     const int rg = rgi < a.nrg ? a.rg_order[rgi] : -1;
+    const int buf_bytes = a.kc * PITCH;
+    // full tiles with aligned rows are staged with asynchronous direct-to-LDS loads; a ragged
+    // last column tile or unaligned pitches go through registers, synchronously
+    const bool fast = a.vec_ok && (col0 + NTW <= a.N);
 
     float4v acc[G][CT];
 #pragma unroll
@@ -204,88 +215,138 @@ __global__ __launch_bounds__(G * CT > 16 ? 512 : 1024) void stripe_kernel(Stripe
 #pragma unroll
         for (int c = 0; c < CT; ++c) acc[j][c] = float4v{0.f, 0.f, 0.f, 0.f};
 
-    // lane's byte offset inside a staged row for its transposed reads: lanes 4e..4e+3 of a
-    // 16-lane group read row e; lane (t mod 4) reads pixels 4*CT*(t mod 4) + 4*ct .. +3
-    const int lane_off = (4 * CT * (lane & 3)) * 2;
-
-    for (int ch = 0; ch < a.nch; ++ch) {
-        const int k0 = ch * kChunkRows;
-        const int rows = min(kChunkRows, a.K - k0);
-        __syncthreads(); // everyone is done reading the previous chunk
-        // ---- stage X[k0 .. k0+rows) x [col0, col0+NTW) in LDS, zero beyond column N
-        constexpr int PIECES = 2 * CT; // 16-byte pieces per row
-        for (int piece = threadIdx.x; piece < rows * PIECES; piece += nthreads) {
-            const int r = piece / PIECES, seg = piece % PIECES;
-            const int c = col0 + seg * 8;
-            const uint16_t *src = a.X + (int64_t)(k0 + r) * a.ldx + c;
-            uint2 lo = {0u, 0u}, hi = {0u, 0u};
-            if (a.vec_ok && c + 8 <= a.N) {
-                const uint4 v = *reinterpret_cast<const uint4 *>(src);
-                lo = uint2{v.x, v.y};
-                hi = uint2{v.z, v.w};
-            } else {
-                uint16_t e[8];
-#pragma unroll
-                for (int t = 0; t < 8; ++t) e[t] = (c + t < a.N) ? src[t] : (uint16_t)0;
-                lo = uint2{(uint32_t)e[0] | ((uint32_t)e[1] << 16), (uint32_t)e[2] | ((uint32_t)e[3] << 16)};
-                hi = uint2{(uint32_t)e[4] | ((uint32_t)e[5] << 16), (uint32_t)e[6] | ((uint32_t)e[7] << 16)};
+    // ---- staging of chunk ch into buffer `buf`
+    auto stage_async = [&](int ch, char *buf) {
+        typedef __attribute__((address_space(3))) void *lptr;
+        typedef __attribute__((address_space(1))) const void *gptr;
+        const int k0 = ch * a.kc;
+        const int rows = min(a.kc, a.K - k0);
+        const int ninst = (rows * PIECES + 63) >> 6; // each instruction fills 1 KB of LDS
+        const int r_in = lane / PIECES, pp = lane % PIECES;
+        for (int i = wave; i < ninst; i += waves) {
+            const int r = i * (64 / PIECES) + r_in;
+            if (r < rows) {
+                const int u = (pp >> 1) ^ swz<CT>(r); // logical unit stored at this position
+                const uint16_t *src = a.X + (int64_t)(k0 + r) * a.ldx + col0 + u * 16 + (pp & 1) * 8;
+                __builtin_amdgcn_global_load_lds((gptr)src, (lptr)(buf + i * 1024), 16, 0, 0);
             }
-            char *dst = smem + r * PITCH + seg * 16;
-            *reinterpret_cast<uint2 *>(dst) = lo;
-            *reinterpret_cast<uint2 *>(dst + 8) = hi;
         }
-        __syncthreads();
-        if (rg < 0) continue;
-        const int s1 = a.seg_ptr[rg * a.nch + ch + 1];
-        for (int s = a.seg_ptr[rg * a.nch + ch]; s < s1; ++s) {
-            const uint32_t meta = a.step_meta[s];
-            const uint32_t lr = a.lane_rows[(int64_t)s * 64 + lane];
-            const int off_lo = (int)(lr & 0xffffu) * PITCH + lane_off;
-            const int off_hi = (int)(lr >> 16) * PITCH + lane_off;
+    };
+    auto stage_sync = [&](int ch, char *buf) {
+        const int k0 = ch * a.kc;
+        const int rows = min(a.kc, a.K - k0);
+        for (int piece = threadIdx.x; piece < rows * PIECES; piece += nthreads) {
+            const int r = piece / PIECES, pp = piece % PIECES;
+            const int u = (pp >> 1) ^ swz<CT>(r);
+            const int c = col0 + u * 16 + (pp & 1) * 8;
+            const uint16_t *src = a.X + (int64_t)(k0 + r) * a.ldx + c;
+            uint4 v;
+            if (a.vec_ok && c + 8 <= a.N) {
+                v = *reinterpret_cast<const uint4 *>(src);
+            } else {
+                uint32_t e[8];
+#pragma unroll
+                for (int t = 0; t < 8; ++t) e[t] = (c + t < a.N) ? (uint32_t)src[t] : 0u;
+                v = uint4{e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16), e[6] | (e[7] << 16)};
+            }
+            *reinterpret_cast<uint4 *>(buf + r * PITCH + pp * 16) = v;
+        }
+    };
+
+    // ---- step stream of this wavefront's row group (contiguous over all chunks)
+    const int seg0 = rg >= 0 ? rg * a.nch : 0;
+    int s = rg >= 0 ? a.seg_ptr[seg0] : 0;
+    const int s_all = rg >= 0 ? a.seg_ptr[seg0 + a.nch] : 0;
+    const uint4 *wbase = reinterpret_cast<const uint4 *>(a.wfrag) + lane;
+    uint32_t meta_n = 0, lr_n = 0;
+    uint4 wf_n[G];
+    auto fetch = [&](int step) {
+        meta_n = a.step_meta[step];
+        lr_n = a.lane_rows[(int64_t)step * 64 + lane];
+        const uint4 *wp = wbase + (int64_t)(meta_n >> 8) * 64;
+        const int nfrag = __builtin_popcount(meta_n & 0xffu);
+#pragma unroll
+        for (int j = 0; j < G; ++j)
+            if (j < nfrag) wf_n[j] = wp[j * 64];
+    };
+    if (s < s_all) fetch(s);
+
+    const int lane_sub = (lane & 3) * 8; // byte offset of this lane's 4 pixels inside a 32-byte unit
+    auto run_steps = [&](const char *buf, int s_end) {
+        while (s < s_end) {
+            const uint32_t meta = meta_n, lr = lr_n;
+            uint4 wf[G];
+#pragma unroll
+            for (int j = 0; j < G; ++j) wf[j] = wf_n[j];
+            if (s + 1 < s_all) fetch(s + 1);
+            const int r_lo = (int)(lr & 0xffffu), r_hi = (int)(lr >> 16);
+            const int b_lo = r_lo * PITCH + lane_sub, b_hi = r_hi * PITCH + lane_sub;
+            const int x_lo = swz<CT>(r_lo) << 5, x_hi = swz<CT>(r_hi) << 5;
             short8v xf[CT];
 #pragma unroll
             for (int c = 0; c < CT; ++c) {
-                const short4v p0 = lds_read_tr(smem, off_lo + c * 8);
-                const short4v p1 = lds_read_tr(smem, off_hi + c * 8);
+                const short4v p0 = lds_read_tr(buf, b_lo + ((c << 5) ^ x_lo));
+                const short4v p1 = lds_read_tr(buf, b_hi + ((c << 5) ^ x_hi));
                 xf[c] = __builtin_shufflevector(p0, p1, 0, 1, 2, 3, 4, 5, 6, 7);
             }
-            const uint4 *wp = reinterpret_cast<const uint4 *>(a.wfrag) + (int64_t)(meta >> 8) * 64 + lane;
+            int f = 0;
 #pragma unroll
             for (int j = 0; j < G; ++j) {
                 if (meta & (1u << j)) {
-                    const short8v wf = __builtin_bit_cast(short8v, *wp);
-                    wp += 64;
+                    // fragments of a step are stored densely in stripe order
+                    uint4 w = wf[0];
 #pragma unroll
-                    for (int c = 0; c < CT; ++c) acc[j][c] = mfma16<BF16>(xf[c], wf, acc[j][c]);
+                    for (int t = 1; t < G; ++t)
+                        if (f == t) w = wf[t];
+                    const short8v wv = __builtin_bit_cast(short8v, w);
+#pragma unroll
+                    for (int c = 0; c < CT; ++c) acc[j][c] = mfma16<BF16>(xf[c], wv, acc[j][c]);
+                    ++f;
                 }
             }
+            ++s;
+        }
+    };
+
+    if (fast) {
+        stage_async(0, smem);
+        for (int ch = 0; ch < a.nch; ++ch) {
+            char *cur = smem + (ch & 1) * buf_bytes;
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __syncthreads(); // chunk ch is in LDS; everyone is done with the other buffer
+            if (ch + 1 < a.nch) stage_async(ch + 1, smem + ((ch + 1) & 1) * buf_bytes);
+            if (rg >= 0) run_steps(cur, a.seg_ptr[seg0 + ch + 1]);
+        }
+    } else {
+        for (int ch = 0; ch < a.nch; ++ch) {
+            if (ch) __syncthreads();
+            stage_sync(ch, smem);
+            __syncthreads();
+            if (rg >= 0) run_steps(smem, a.seg_ptr[seg0 + ch + 1]);
         }
     }
 
-    // ---- store: lane (g = lane/16, n = lane%16) holds pixels col0 + 4*CT*g + 4*ct + v of
-    // row 16*(G*rg + j) + n.  Rows no block touches are stored as zeros like any other.
+    // ---- store: lane (g = lane/16, n = lane%16) holds pixels col0 + 16*c + 4*g + v of row
+    // 16*(G*rg + j) + n.  Rows no block touches are stored as zeros like any other.
     if (rg < 0) return;
     const int g = lane >> 4, n = lane & 15;
-    const int px0 = col0 + 4 * CT * g;
-    if (px0 >= a.N) return;
     TY *Yt = static_cast<TY *>(a.Y);
 #pragma unroll
     for (int j = 0; j < G; ++j) {
         const int row = (rg * G + j) * kStripe + n;
         if (row >= a.M) continue;
-        TY *dst = Yt + (int64_t)row * a.ldy + px0;
-        if (a.vec_ok && px0 + 4 * CT <= a.N) {
 #pragma unroll
-            for (int c = 0; c < CT; ++c) {
+        for (int c = 0; c < CT; ++c) {
+            const int px = col0 + 16 * c + 4 * g;
+            TY *dst = Yt + (int64_t)row * a.ldy + px;
+            if (a.vec_ok && px + 4 <= a.N) {
                 float v[4] = {acc[j][c][0], acc[j][c][1], acc[j][c][2], acc[j][c][3]};
-                store_row<TY, 4>(dst + 4 * c, v);
-            }
-        } else {
-#pragma unroll
-            for (int c = 0; c < CT; ++c)
+                store_row<TY, 4>(dst, v);
+            } else {
 #pragma unroll
                 for (int v = 0; v < 4; ++v)
-                    if (px0 + 4 * c + v < a.N) dst[4 * c + v] = from_f32<TY>(acc[j][c][v]);
+                    if (px + v < a.N) dst[v] = from_f32<TY>(acc[j][c][v]);
+            }
         }
     }
 }
@@ -324,14 +385,16 @@ ubp_status launch_wros(const ubp_packed *p, const void *X, int64_t ldx, int N, v
 
 template <bool BF16, typename TY, int G, int CT>
 ubp_status launch_stripe_inst(const StripeArgs &a, int waves, hipStream_t st) {
-    constexpr int PITCH = 16 * CT * 2 + 8;
-    const size_t lds = (size_t)kChunkRows * PITCH;
-    static bool attr_set = false; // per instantiation; raising the limit is idempotent
-    if (!attr_set) {
+    // two chunk buffers when there is more than one chunk
+    const size_t lds = (size_t)a.kc * (32 * CT) * (a.nch > 1 ? 2 : 1);
+    static size_t attr_bytes = 0; // per instantiation; the limit is only ever raised
+    if (lds > attr_bytes) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(&stripe_kernel<BF16, TY, G, CT>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
+            (void)hipGetLastError();
             return UBP_ERR_DEVICE;
-        attr_set = true;
+        }
+        attr_bytes = lds;
     }
     const unsigned grid = 8u * (unsigned)((a.n_coltiles + 7) / 8) * (unsigned)a.n_wgrows;
     hipLaunchKernelGGL((stripe_kernel<BF16, TY, G, CT>), dim3(grid), dim3((unsigned)waves * 64), lds, st, a);
@@ -343,7 +406,8 @@ ubp_status launch_stripe(const StripeArgs &a, int G, int CT, int waves, hipStrea
     if (G * CT > 16 && waves > 8) return UBP_ERR_UNSUPPORTED;
 #define UBP_SG_CASE(GG, CC) \
     if (G == GG && CT == CC) return launch_stripe_inst<BF16, TY, GG, CC>(a, waves, st);
-    UBP_SG_CASE(1, 4) UBP_SG_CASE(2, 4) UBP_SG_CASE(4, 4) UBP_SG_CASE(1, 8) UBP_SG_CASE(2, 8) UBP_SG_CASE(4, 8)
+    UBP_SG_CASE(1, 2) UBP_SG_CASE(2, 2) UBP_SG_CASE(4, 2) UBP_SG_CASE(1, 4) UBP_SG_CASE(2, 4) UBP_SG_CASE(4, 4)
+    UBP_SG_CASE(1, 8) UBP_SG_CASE(2, 8) UBP_SG_CASE(4, 8)
 #undef UBP_SG_CASE
     return UBP_ERR_UNSUPPORTED;
 }
@@ -393,7 +457,7 @@ ubp_status upload(ubp_packed *p) {
         ok = ok && dev_copy(&p->d_values_f32, f.data(), f.size(), &p->device_bytes);
     }
     if (p->dtype != UBP_F32) {
-        for (int s = 0; s < kNumG && ok; ++s) {
+        for (int s = 0; s < kNumLayouts && ok; ++s) {
             const StripeLayout &L = p->sg[s];
             StripeLayoutDev &D = p->d_sg[s];
             ok = ok && dev_copy(&D.seg_ptr, L.seg_ptr.data(), L.seg_ptr.size(), &p->device_bytes);
@@ -421,7 +485,7 @@ void release_device(ubp_packed *p) {
     rel(p->d_indptr);
     rel(p->d_indices);
     rel(p->d_values_f32);
-    for (int s = 0; s < kNumG; ++s) {
+    for (int s = 0; s < kNumLayouts; ++s) {
         rel(p->d_sg[s].seg_ptr);
         rel(p->d_sg[s].rg_order);
         rel(p->d_sg[s].step_meta);
@@ -485,6 +549,7 @@ ubp_status ubp_spmm_plan(const ubp_packed *p, const void *X_dev, int64_t ldx, in
     int CT = pl.col_tiles ? pl.col_tiles : env_int("UBP_CT", 0);
     int G = pl.sub_stripes ? pl.sub_stripes : env_int("UBP_G", 0);
     int waves = pl.waves ? pl.waves : env_int("UBP_WAVES", 0);
+    int KC = pl.chunk_rows ? pl.chunk_rows : env_int("UBP_KC", 0);
     if (CT == 0) CT = 4;
     if (G == 0) {
         // largest row group that still leaves about two wavefront tiles per SIMD
@@ -492,10 +557,16 @@ ubp_status ubp_spmm_plan(const ubp_packed *p, const void *X_dev, int64_t ldx, in
         G = 4;
         while (G > 1 && ((p->M + 16 * G - 1) / (16 * G)) * coltiles < 2048) G >>= 1;
     }
-    if (G != 1 && G != 2 && G != 4) return UBP_ERR_UNSUPPORTED;
-    if (CT != 4 && CT != 8) return UBP_ERR_UNSUPPORTED;
-    const int slot = G == 1 ? 0 : (G == 2 ? 1 : 2);
+    if (CT != 2 && CT != 4 && CT != 8) return UBP_ERR_UNSUPPORTED;
+    if (KC == 0) {
+        // largest chunk whose two buffers fit 128 KB of LDS, not larger than K needs
+        KC = 2048 / CT;
+        while (KC > 128 && KC / 2 >= p->K) KC >>= 1;
+    }
+    const int slot = layout_slot(G, KC);
+    if (slot < 0) return UBP_ERR_UNSUPPORTED;
     const StripeLayout &L = p->sg[slot];
+    if ((size_t)KC * 32 * CT * (L.nch > 1 ? 2 : 1) > 160 * 1024) return UBP_ERR_UNSUPPORTED;
     const int max_waves = (G * CT > 16) ? 8 : 16;
     if (waves == 0) waves = std::min(max_waves, std::max(1, L.nrg));
     if (waves < 1 || waves > max_waves) return UBP_ERR_UNSUPPORTED;
@@ -515,6 +586,7 @@ ubp_status ubp_spmm_plan(const ubp_packed *p, const void *X_dev, int64_t ldx, in
     a.N = N;
     a.nrg = L.nrg;
     a.nch = L.nch;
+    a.kc = L.chunk_rows;
     a.n_coltiles = (N + 16 * CT - 1) / (16 * CT);
     a.n_wgrows = (L.nrg + waves - 1) / waves;
     const size_t ysz = (y_dtype == UBP_F32) ? 4 : 2;

@@ -42,6 +42,7 @@ SMALL = [  # M, K, N, bh, bw, density: several tiles, ragged tails, odd pitches
     (130, 600, 1000, 16, 16, 0.15),
     (33, 40, 129, 5, 3, 0.3),
     (48, 520, 72, 2, 6, 0.35),
+    (96, 700, 256, 4, 4, 0.25),
     (16, 16, 16, 16, 16, 1.0),
     (257, 31, 40, 1, 1, 0.3),
 ]
@@ -65,10 +66,14 @@ def test_stripe_kernel_small(shape, dtype):
     M, K, N, bh, bw, d = shape
     blocks, W, X = _layer(M, K, N, bh, bw, d, dtype, seed=M + K + 1)
     Yref, Yabs = _oracle(W, dtype, bh, bw, blocks, X)
-    for G, CT in itertools.product((1, 2, 4), (4, 8)):
+    for G, CT in itertools.product((1, 2, 4), (2, 4, 8)):
         for y_dtype in (dtype, "f32"):
             Y = run_spmm(W, dtype, bh, bw, blocks, X, y_dtype, _plan(kernel=2, sub_stripes=G, col_tiles=CT))
             check(Y, Yref, Yabs, dtype, y_dtype)
+    for G, CT, KC in [(1, 4, 128), (2, 2, 256), (4, 8, 128), (2, 4, 512), (1, 2, 1024)]:
+        Y = run_spmm(W, dtype, bh, bw, blocks, X, dtype,
+                     _plan(kernel=2, sub_stripes=G, col_tiles=CT, chunk_rows=KC))
+        check(Y, Yref, Yabs, dtype)
     Y = run_spmm(W, dtype, bh, bw, blocks, X, dtype, _plan(kernel=2, sub_stripes=1, col_tiles=4, waves=3))
     check(Y, Yref, Yabs, dtype)
 
