@@ -131,7 +131,7 @@ ubp_status ubp_spmm(const ubp_packed *p, const void *X_dev, int64_t ldx, int32_t
  *   col_tiles  : MFMA kernel, 16-column tiles per wavefront (2, 4 or 8).
  *   waves      : wavefronts per workgroup (1..16).
  *   rows_per_range : WROS kernel, output rows owned by one workgroup row (multiple of bh).
- *   chunk_rows : MFMA kernel, rows of X staged in LDS at a time (128, 256, 512 or 1024).
+ *   chunk_rows : MFMA kernel, rows of X staged in LDS at a time (256, 512 or 1024).
  */
 typedef struct {
     int32_t kernel, sub_stripes, col_tiles, waves, rows_per_range, chunk_rows, reserved[2];

@@ -317,9 +317,9 @@ static void build_one(ubp_packed *p, StripeLayout &L, int G, int kChunkRows) {
     L.nrg = (M + rgh - 1) / rgh;
     L.nch = (K + kChunkRows - 1) / kChunkRows;
     L.seg_ptr.assign((size_t)L.nrg * L.nch + 1, 0);
-    L.step_meta.clear();
-    L.lane_rows.clear();
-    L.wfrag.clear();
+    L.stream.clear();
+    L.nsteps = 0;
+    const size_t rec_dw = 64 + 256 * (size_t)G;
     L.total_mfma = 0;
     const uint16_t *vals = reinterpret_cast<const uint16_t *>(p->values.data());
     const int32_t nstart = M - bh + 1; // start rows 0..M-bh
@@ -362,15 +362,15 @@ static void build_one(ubp_packed *p, StripeLayout &L, int G, int kChunkRows) {
         });
         size_t pos = 0;
         for (int ch = 0; ch < L.nch; ++ch) {
-            L.seg_ptr[(size_t)rg * L.nch + ch] = (int32_t)L.step_meta.size();
+            L.seg_ptr[(size_t)rg * L.nch + ch] = (int32_t)L.nsteps;
             size_t end = pos;
             while (end < entries.size() && entries[end].k / kChunkRows == ch) ++end;
             for (size_t s = pos; s < end; s += kStep) {
                 const size_t n = std::min<size_t>(kStep, end - s);
                 uint32_t mask = 0;
                 for (size_t e = 0; e < n; ++e) mask |= entries[s + e].mask;
-                const uint32_t first_frag = (uint32_t)(L.wfrag.size() / (64 * 8));
-                L.step_meta.push_back((first_frag << 8) | mask);
+                const size_t rec = L.stream.size();
+                L.stream.resize(rec + rec_dw, 0u);
                 // X rows gathered by this step, chunk-relative; padding repeats the first row
                 int32_t rows[kStep];
                 for (size_t e = 0; e < (size_t)kStep; ++e)
@@ -379,29 +379,31 @@ static void build_one(ubp_packed *p, StripeLayout &L, int G, int kChunkRows) {
                 for (int lane = 0; lane < 64; ++lane) {
                     const int g = lane / 16, t = lane % 16;
                     const uint32_t lo = (uint32_t)rows[8 * g + t / 4], hi = (uint32_t)rows[8 * g + 4 + t / 4];
-                    L.lane_rows.push_back(lo | (hi << 16));
+                    L.stream[rec + lane] = lo | (hi << 10) | (mask << 20);
                 }
                 // weight fragments: lane (n = lane mod 16, g = lane / 16) holds row 16*j + n,
                 // entries 8g .. 8g+7
+                uint16_t *frag = reinterpret_cast<uint16_t *>(&L.stream[rec + 64]);
                 for (int j = 0; j < G; ++j) {
                     if (!(mask & (1u << j))) continue;
                     for (int lane = 0; lane < 64; ++lane) {
                         const int g = lane / 16, nrow = lane % 16;
                         for (int e = 0; e < 8; ++e) {
                             const size_t idx = (size_t)(8 * g + e);
-                            uint16_t v = 0;
-                            if (idx < n) v = wbuf[(size_t)entries[s + idx].slot * rgh + (kStripe * j + nrow)];
-                            L.wfrag.push_back(v);
+                            if (idx < n)
+                                frag[((size_t)j * 64 + lane) * 8 + e] =
+                                    wbuf[(size_t)entries[s + idx].slot * rgh + (kStripe * j + nrow)];
                         }
                     }
                     ++L.total_mfma;
                     ++rg_weight[(size_t)rg];
                 }
+                ++L.nsteps;
             }
             pos = end;
         }
     }
-    L.seg_ptr[(size_t)L.nrg * L.nch] = (int32_t)L.step_meta.size();
+    L.seg_ptr[(size_t)L.nrg * L.nch] = (int32_t)L.nsteps;
     L.rg_order.resize((size_t)L.nrg);
     std::iota(L.rg_order.begin(), L.rg_order.end(), 0);
     std::stable_sort(L.rg_order.begin(), L.rg_order.end(),

@@ -11,17 +11,17 @@ namespace ubp {
 constexpr int kStripe = 16;     // rows of one MFMA output tile (aligned row stripe)
 constexpr int kStep = 32;       // gathered X rows consumed by one 16x16x32 MFMA
 constexpr int kNumG = 3;        // stripes per wavefront: 1, 2, 4
-constexpr int kNumKC = 4;       // X rows staged in LDS per chunk: 128, 256, 512, 1024
+constexpr int kNumKC = 3;       // X rows staged in LDS per chunk: 256, 512, 1024
 constexpr int kNumLayouts = kNumG * kNumKC;
 
 // A layout is built for every (G, chunk rows) pair the launcher can choose.
 inline int layout_slot(int G, int KC) {
     const int gi = G == 1 ? 0 : G == 2 ? 1 : G == 4 ? 2 : -1;
-    const int ki = KC == 128 ? 0 : KC == 256 ? 1 : KC == 512 ? 2 : KC == 1024 ? 3 : -1;
+    const int ki = KC == 256 ? 0 : KC == 512 ? 1 : KC == 1024 ? 2 : -1;
     return (gi < 0 || ki < 0) ? -1 : gi * kNumKC + ki;
 }
 inline int slot_G(int slot) { return 1 << (slot / kNumKC); }
-inline int slot_KC(int slot) { return 128 << (slot % kNumKC); }
+inline int slot_KC(int slot) { return 256 << (slot % kNumKC); }
 
 // Host image of the MFMA kernel's private re-layout of the packed weights, for one
 // choice of G (16-row stripes handled together by one wavefront).
@@ -38,18 +38,21 @@ struct StripeLayout {
     int nch = 0;     // chunks of X rows
     std::vector<int32_t> seg_ptr;    // [nrg*nch + 1] first step of (row group, chunk)
     std::vector<int32_t> rg_order;   // row groups, heaviest (most MFMAs) first
-    std::vector<uint32_t> step_meta; // [steps] low 8 bits: stripes with nonzero weights; high 24: first fragment
-    std::vector<uint32_t> lane_rows; // [steps*64] per lane: chunk-relative X rows of its two transposed LDS reads
-    std::vector<uint16_t> wfrag;     // [fragments*64*8] weight fragments in MFMA operand order (16-bit patterns)
-    int64_t total_mfma = 0;          // fragments (one per 16-column tile per step and stripe)
+    // One fixed-size record per step, (64 + 256*G) dwords, so that the address of any later
+    // step is known without reading metadata:
+    //   dwords 0..63      : per lane, bits 0-9 / 10-19 = chunk-relative X rows of the lane's two
+    //                       transposed LDS reads, bits 20-23 = stripes with nonzero weights
+    //   then G x 256 dwords: weight fragment of stripe j in MFMA operand order (lane-major,
+    //                       8 16-bit values per lane), all zero when the step has no weight there
+    std::vector<uint32_t> stream;
+    int64_t nsteps = 0;
+    int64_t total_mfma = 0;          // MFMA issues per 16-column tile (steps x stripes with weights)
 };
 
 struct StripeLayoutDev {
     int32_t *seg_ptr = nullptr;
     int32_t *rg_order = nullptr;
-    uint32_t *step_meta = nullptr;
-    uint32_t *lane_rows = nullptr;
-    uint16_t *wfrag = nullptr;
+    uint32_t *stream = nullptr;
 };
 
 } // namespace ubp

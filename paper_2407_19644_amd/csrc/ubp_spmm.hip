@@ -140,9 +140,7 @@ __global__ __launch_bounds__(256) void wros_kernel(const int32_t *__restrict__ i
 struct StripeArgs {
     const int32_t *seg_ptr;
     const int32_t *rg_order;
-    const uint32_t *step_meta;
-    const uint32_t *lane_rows;
-    const uint16_t *wfrag;
+    const uint32_t *stream;
     const uint16_t *X;
     void *Y;
     int64_t ldx, ldy;
@@ -173,19 +171,34 @@ template <int CT> __device__ __forceinline__ int swz(int row) {
     else return row & 3;
 }
 
+template <int N> __device__ __forceinline__ void wait_vmcnt() {
+    static_assert(N >= 0 && N < 64, "vmcnt immediate out of range");
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+constexpr int stripe_max_threads(int G, int CT, int D) {
+    // accumulators + operand fragments + D prefetched step records, in VGPRs per lane
+    return (4 * G * CT + 4 * CT + D * (1 + 4 * G) + 24) <= 128 ? 1024 : 512;
+}
+
 // One workgroup = `waves` wavefronts that share one tile of 16*CT columns of X / Y; each
 // wavefront owns one row group (G aligned 16-row stripes) and keeps its G*CT output tiles
-// in fp32 accumulators for the whole K loop (output stationary).  X is staged chunk by
-// chunk in a double-buffered LDS region with direct global->LDS loads issued one chunk
-// ahead; a step gathers 32 staged rows with two transposed LDS reads per lane and column
-// tile and issues one 16x16x32 MFMA per (stripe with nonzero weights, column tile).  The
-// product is formed transposed (pixels x rows) so that a lane holds 4 consecutive pixels
-// of one output row.  Step metadata and weight fragments are fetched one step ahead.
-template <bool BF16, typename TY, int G, int CT>
-__global__ __launch_bounds__(G * CT > 16 ? 512 : 1024) void stripe_kernel(StripeArgs a) {
-    constexpr int NTW = 16 * CT;  // columns per workgroup
+// in fp32 accumulators for the whole K loop (output stationary).
+//  * X is staged chunk by chunk in a double-buffered LDS region with direct global->LDS
+//    loads issued one chunk ahead.
+//  * The wavefront's steps form one contiguous stream of fixed-size records (gather rows +
+//    weight fragments); records are fetched D steps ahead into a register ring, so the
+//    stream's memory latency is off the critical path.
+//  * A step gathers 32 staged rows with two transposed LDS reads per lane and column tile
+//    and issues one 16x16x32 MFMA per (stripe with nonzero weights, column tile).  The
+//    product is formed transposed (pixels x rows) so that a lane holds 4 consecutive
+//    pixels of one output row.
+template <bool BF16, typename TY, int G, int CT, int D>
+__global__ __launch_bounds__(stripe_max_threads(G, CT, D)) void stripe_kernel(StripeArgs a) {
+    constexpr int NTW = 16 * CT;   // columns per workgroup
     constexpr int PITCH = NTW * 2; // bytes per staged row
     constexpr int PIECES = 2 * CT; // 16-byte pieces per staged row
+    constexpr int REC_DW = 64 + 256 * G;
     extern __shared__ __attribute__((aligned(1024))) char smem[];
 
     // workgroup -> (column tile, workgroup row); consecutive workgroup ids go round-robin
@@ -253,76 +266,81 @@ __global__ __launch_bounds__(G * CT > 16 ? 512 : 1024) void stripe_kernel(Stripe
         }
     };
 
-    // ---- step stream of this wavefront's row group (contiguous over all chunks)
+    // ---- this wavefront's step stream (contiguous over all chunks) and its register ring
     const int seg0 = rg >= 0 ? rg * a.nch : 0;
     int s = rg >= 0 ? a.seg_ptr[seg0] : 0;
     const int s_all = rg >= 0 ? a.seg_ptr[seg0 + a.nch] : 0;
-    const uint4 *wbase = reinterpret_cast<const uint4 *>(a.wfrag) + lane;
-    uint32_t meta_n = 0, lr_n = 0;
-    uint4 wf_n[G];
-    auto fetch = [&](int step) {
-        meta_n = a.step_meta[step];
-        lr_n = a.lane_rows[(int64_t)step * 64 + lane];
-        const uint4 *wp = wbase + (int64_t)(meta_n >> 8) * 64;
-        const int nfrag = __builtin_popcount(meta_n & 0xffu);
+    uint32_t info[D];
+    uint4 wf[D][G];
+    auto issue = [&](int d, int step) {
+        const uint32_t *rec = a.stream + (int64_t)step * REC_DW;
+        info[d] = rec[lane];
+        const uint4 *fr = reinterpret_cast<const uint4 *>(rec + 64) + lane;
 #pragma unroll
-        for (int j = 0; j < G; ++j)
-            if (j < nfrag) wf_n[j] = wp[j * 64];
+        for (int j = 0; j < G; ++j) wf[d][j] = fr[j * 64];
     };
-    if (s < s_all) fetch(s);
+#pragma unroll
+    for (int d = 0; d < D; ++d)
+        if (s + d < s_all) issue(d, s + d);
+
+    int ch = -1, s_end = s, since_stage = 0;
+    const char *cur = smem;
+    if (fast) stage_async(0, smem);
+    auto advance = [&]() { // make chunk ch+1 the current one
+        ++ch;
+        if (fast) {
+            // the staging loads of this chunk were issued before the last `since_stage` record
+            // fetches; vector memory operations complete in order, so once at most D records
+            // (1 + G loads each) are outstanding the staged chunk has landed
+            if (since_stage >= D) wait_vmcnt<D * (1 + G)>();
+            else wait_vmcnt<0>();
+            __syncthreads(); // chunk ch is in LDS for everyone; the other buffer is free
+            if (ch + 1 < a.nch) stage_async(ch + 1, smem + ((ch + 1) & 1) * buf_bytes);
+            since_stage = 0;
+            cur = smem + (ch & 1) * buf_bytes;
+        } else {
+            if (ch) __syncthreads();
+            stage_sync(ch, smem);
+            __syncthreads();
+        }
+        s_end = rg >= 0 ? a.seg_ptr[seg0 + ch + 1] : 0;
+    };
 
     const int lane_sub = (lane & 3) * 8; // byte offset of this lane's 4 pixels inside a 32-byte unit
-    auto run_steps = [&](const char *buf, int s_end) {
-        while (s < s_end) {
-            const uint32_t meta = meta_n, lr = lr_n;
-            uint4 wf[G];
+    bool done = false;
+    while (!done) {
 #pragma unroll
-            for (int j = 0; j < G; ++j) wf[j] = wf_n[j];
-            if (s + 1 < s_all) fetch(s + 1);
-            const int r_lo = (int)(lr & 0xffffu), r_hi = (int)(lr >> 16);
+        for (int d = 0; d < D; ++d) {
+            while (s >= s_end && ch + 1 < a.nch) advance();
+            if (s >= s_all) {
+                done = true;
+                break;
+            }
+            const uint32_t inf = info[d];
+            const int r_lo = (int)(inf & 0x3ffu), r_hi = (int)((inf >> 10) & 0x3ffu);
+            const uint32_t mask = __builtin_amdgcn_readfirstlane(inf >> 20);
             const int b_lo = r_lo * PITCH + lane_sub, b_hi = r_hi * PITCH + lane_sub;
             const int x_lo = swz<CT>(r_lo) << 5, x_hi = swz<CT>(r_hi) << 5;
             short8v xf[CT];
 #pragma unroll
             for (int c = 0; c < CT; ++c) {
-                const short4v p0 = lds_read_tr(buf, b_lo + ((c << 5) ^ x_lo));
-                const short4v p1 = lds_read_tr(buf, b_hi + ((c << 5) ^ x_hi));
+                const short4v p0 = lds_read_tr(cur, b_lo + ((c << 5) ^ x_lo));
+                const short4v p1 = lds_read_tr(cur, b_hi + ((c << 5) ^ x_hi));
                 xf[c] = __builtin_shufflevector(p0, p1, 0, 1, 2, 3, 4, 5, 6, 7);
             }
-            int f = 0;
 #pragma unroll
             for (int j = 0; j < G; ++j) {
-                if (meta & (1u << j)) {
-                    // fragments of a step are stored densely in stripe order
-                    uint4 w = wf[0];
-#pragma unroll
-                    for (int t = 1; t < G; ++t)
-                        if (f == t) w = wf[t];
-                    const short8v wv = __builtin_bit_cast(short8v, w);
+                if (G == 1 || (mask & (1u << j))) {
+                    const short8v wv = __builtin_bit_cast(short8v, wf[d][j]);
 #pragma unroll
                     for (int c = 0; c < CT; ++c) acc[j][c] = mfma16<BF16>(xf[c], wv, acc[j][c]);
-                    ++f;
                 }
             }
+            if (s + D < s_all) {
+                issue(d, s + D);
+                ++since_stage;
+            }
             ++s;
-        }
-    };
-
-    if (fast) {
-        stage_async(0, smem);
-        for (int ch = 0; ch < a.nch; ++ch) {
-            char *cur = smem + (ch & 1) * buf_bytes;
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-            __syncthreads(); // chunk ch is in LDS; everyone is done with the other buffer
-            if (ch + 1 < a.nch) stage_async(ch + 1, smem + ((ch + 1) & 1) * buf_bytes);
-            if (rg >= 0) run_steps(cur, a.seg_ptr[seg0 + ch + 1]);
-        }
-    } else {
-        for (int ch = 0; ch < a.nch; ++ch) {
-            if (ch) __syncthreads();
-            stage_sync(ch, smem);
-            __syncthreads();
-            if (rg >= 0) run_steps(smem, a.seg_ptr[seg0 + ch + 1]);
         }
     }
 
@@ -383,13 +401,17 @@ ubp_status launch_wros(const ubp_packed *p, const void *X, int64_t ldx, int N, v
                : launch_wros_bh<TX, TY, 1>(p, X, ldx, N, Y, ldy, rpr, st);
 }
 
+constexpr int kPrefetchDepth = 4;
+
 template <bool BF16, typename TY, int G, int CT>
 ubp_status launch_stripe_inst(const StripeArgs &a, int waves, hipStream_t st) {
+    constexpr int D = kPrefetchDepth;
+    if (waves * 64 > stripe_max_threads(G, CT, D)) return UBP_ERR_UNSUPPORTED;
     // two chunk buffers when there is more than one chunk
     const size_t lds = (size_t)a.kc * (32 * CT) * (a.nch > 1 ? 2 : 1);
     static size_t attr_bytes = 0; // per instantiation; the limit is only ever raised
     if (lds > attr_bytes) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&stripe_kernel<BF16, TY, G, CT>),
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&stripe_kernel<BF16, TY, G, CT, D>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
             (void)hipGetLastError();
             return UBP_ERR_DEVICE;
@@ -397,13 +419,12 @@ ubp_status launch_stripe_inst(const StripeArgs &a, int waves, hipStream_t st) {
         attr_bytes = lds;
     }
     const unsigned grid = 8u * (unsigned)((a.n_coltiles + 7) / 8) * (unsigned)a.n_wgrows;
-    hipLaunchKernelGGL((stripe_kernel<BF16, TY, G, CT>), dim3(grid), dim3((unsigned)waves * 64), lds, st, a);
+    hipLaunchKernelGGL((stripe_kernel<BF16, TY, G, CT, D>), dim3(grid), dim3((unsigned)waves * 64), lds, st, a);
     return hipGetLastError() == hipSuccess ? UBP_OK : UBP_ERR_DEVICE;
 }
 
 template <bool BF16, typename TY>
 ubp_status launch_stripe(const StripeArgs &a, int G, int CT, int waves, hipStream_t st) {
-    if (G * CT > 16 && waves > 8) return UBP_ERR_UNSUPPORTED;
 #define UBP_SG_CASE(GG, CC) \
     if (G == GG && CT == CC) return launch_stripe_inst<BF16, TY, GG, CC>(a, waves, st);
     UBP_SG_CASE(1, 2) UBP_SG_CASE(2, 2) UBP_SG_CASE(4, 2) UBP_SG_CASE(1, 4) UBP_SG_CASE(2, 4) UBP_SG_CASE(4, 4)
@@ -411,6 +432,8 @@ ubp_status launch_stripe(const StripeArgs &a, int G, int CT, int waves, hipStrea
 #undef UBP_SG_CASE
     return UBP_ERR_UNSUPPORTED;
 }
+
+int stripe_max_waves(int G, int CT) { return stripe_max_threads(G, CT, kPrefetchDepth) / 64; }
 
 int env_int(const char *name, int dflt) {
     const char *v = std::getenv(name);
@@ -462,9 +485,7 @@ ubp_status upload(ubp_packed *p) {
             StripeLayoutDev &D = p->d_sg[s];
             ok = ok && dev_copy(&D.seg_ptr, L.seg_ptr.data(), L.seg_ptr.size(), &p->device_bytes);
             ok = ok && dev_copy(&D.rg_order, L.rg_order.data(), L.rg_order.size(), &p->device_bytes);
-            ok = ok && dev_copy(&D.step_meta, L.step_meta.data(), L.step_meta.size(), &p->device_bytes);
-            ok = ok && dev_copy(&D.lane_rows, L.lane_rows.data(), L.lane_rows.size(), &p->device_bytes);
-            ok = ok && dev_copy(&D.wfrag, L.wfrag.data(), L.wfrag.size(), &p->device_bytes);
+            ok = ok && dev_copy(&D.stream, L.stream.data(), L.stream.size(), &p->device_bytes);
         }
     }
     if (!ok) {
@@ -488,9 +509,7 @@ void release_device(ubp_packed *p) {
     for (int s = 0; s < kNumLayouts; ++s) {
         rel(p->d_sg[s].seg_ptr);
         rel(p->d_sg[s].rg_order);
-        rel(p->d_sg[s].step_meta);
-        rel(p->d_sg[s].lane_rows);
-        rel(p->d_sg[s].wfrag);
+        rel(p->d_sg[s].stream);
     }
 }
 
@@ -561,22 +580,20 @@ ubp_status ubp_spmm_plan(const ubp_packed *p, const void *X_dev, int64_t ldx, in
     if (KC == 0) {
         // largest chunk whose two buffers fit 128 KB of LDS, not larger than K needs
         KC = 2048 / CT;
-        while (KC > 128 && KC / 2 >= p->K) KC >>= 1;
+        while (KC > 256 && KC / 2 >= p->K) KC >>= 1;
     }
     const int slot = layout_slot(G, KC);
     if (slot < 0) return UBP_ERR_UNSUPPORTED;
     const StripeLayout &L = p->sg[slot];
     if ((size_t)KC * 32 * CT * (L.nch > 1 ? 2 : 1) > 160 * 1024) return UBP_ERR_UNSUPPORTED;
-    const int max_waves = (G * CT > 16) ? 8 : 16;
+    const int max_waves = stripe_max_waves(G, CT);
     if (waves == 0) waves = std::min(max_waves, std::max(1, L.nrg));
     if (waves < 1 || waves > max_waves) return UBP_ERR_UNSUPPORTED;
 
     StripeArgs a;
     a.seg_ptr = p->d_sg[slot].seg_ptr;
     a.rg_order = p->d_sg[slot].rg_order;
-    a.step_meta = p->d_sg[slot].step_meta;
-    a.lane_rows = p->d_sg[slot].lane_rows;
-    a.wfrag = p->d_sg[slot].wfrag;
+    a.stream = p->d_sg[slot].stream;
     a.X = static_cast<const uint16_t *>(X_dev);
     a.Y = Y_dev;
     a.ldx = ldx;

@@ -70,7 +70,7 @@ def test_stripe_kernel_small(shape, dtype):
         for y_dtype in (dtype, "f32"):
             Y = run_spmm(W, dtype, bh, bw, blocks, X, y_dtype, _plan(kernel=2, sub_stripes=G, col_tiles=CT))
             check(Y, Yref, Yabs, dtype, y_dtype)
-    for G, CT, KC in [(1, 4, 128), (2, 2, 256), (4, 8, 128), (2, 4, 512), (1, 2, 1024)]:
+    for G, CT, KC in [(1, 4, 256), (2, 2, 256), (4, 8, 256), (2, 4, 512), (1, 2, 1024)]:
         Y = run_spmm(W, dtype, bh, bw, blocks, X, dtype,
                      _plan(kernel=2, sub_stripes=G, col_tiles=CT, chunk_rows=KC))
         check(Y, Yref, Yabs, dtype)
