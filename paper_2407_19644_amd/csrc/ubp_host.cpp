@@ -316,7 +316,7 @@ static void build_one(ubp_packed *p, StripeLayout &L, int G, int kChunkRows) {
     L.chunk_rows = kChunkRows;
     L.nrg = (M + rgh - 1) / rgh;
     L.nch = (K + kChunkRows - 1) / kChunkRows;
-    L.seg_ptr.assign((size_t)L.nrg * L.nch + 1, 0);
+    L.rg_ptr.assign((size_t)L.nrg + 1, 0);
     L.stream.clear();
     L.nsteps = 0;
     const size_t rec_dw = 64 + 256 * (size_t)G;
@@ -361,10 +361,15 @@ static void build_one(ubp_packed *p, StripeLayout &L, int G, int kChunkRows) {
             return a.k < b.k;
         });
         size_t pos = 0;
+        L.rg_ptr[(size_t)rg] = (int32_t)L.nsteps;
         for (int ch = 0; ch < L.nch; ++ch) {
-            L.seg_ptr[(size_t)rg * L.nch + ch] = (int32_t)L.nsteps;
             size_t end = pos;
             while (end < entries.size() && entries[end].k / kChunkRows == ch) ++end;
+            if (end == pos) { // no weights in this chunk: one step that only carries the chunk-end flag
+                L.stream.resize(L.stream.size() + rec_dw, 0u);
+                for (int lane = 0; lane < 64; ++lane) L.stream[L.stream.size() - rec_dw + lane] = 1u << 24;
+                ++L.nsteps;
+            }
             for (size_t s = pos; s < end; s += kStep) {
                 const size_t n = std::min<size_t>(kStep, end - s);
                 uint32_t mask = 0;
@@ -379,7 +384,8 @@ static void build_one(ubp_packed *p, StripeLayout &L, int G, int kChunkRows) {
                 for (int lane = 0; lane < 64; ++lane) {
                     const int g = lane / 16, t = lane % 16;
                     const uint32_t lo = (uint32_t)rows[8 * g + t / 4], hi = (uint32_t)rows[8 * g + 4 + t / 4];
-                    L.stream[rec + lane] = lo | (hi << 10) | (mask << 20);
+                    const uint32_t last = (s + kStep >= end) ? (1u << 24) : 0u;
+                    L.stream[rec + lane] = lo | (hi << 10) | (mask << 20) | last;
                 }
                 // weight fragments: lane (n = lane mod 16, g = lane / 16) holds row 16*j + n,
                 // entries 8g .. 8g+7
@@ -403,7 +409,7 @@ static void build_one(ubp_packed *p, StripeLayout &L, int G, int kChunkRows) {
             pos = end;
         }
     }
-    L.seg_ptr[(size_t)L.nrg * L.nch] = (int32_t)L.nsteps;
+    L.rg_ptr[(size_t)L.nrg] = (int32_t)L.nsteps;
     L.rg_order.resize((size_t)L.nrg);
     std::iota(L.rg_order.begin(), L.rg_order.end(), 0);
     std::stable_sort(L.rg_order.begin(), L.rg_order.end(),

@@ -36,12 +36,14 @@ struct StripeLayout {
     int chunk_rows = 0; // X rows per LDS chunk
     int nrg = 0;     // row groups
     int nch = 0;     // chunks of X rows
-    std::vector<int32_t> seg_ptr;    // [nrg*nch + 1] first step of (row group, chunk)
+    std::vector<int32_t> rg_ptr;     // [nrg + 1] first step of each row group
     std::vector<int32_t> rg_order;   // row groups, heaviest (most MFMAs) first
     // One fixed-size record per step, (64 + 256*G) dwords, so that the address of any later
     // step is known without reading metadata:
     //   dwords 0..63      : per lane, bits 0-9 / 10-19 = chunk-relative X rows of the lane's two
-    //                       transposed LDS reads, bits 20-23 = stripes with nonzero weights
+    //                       transposed LDS reads, bits 20-23 = stripes with nonzero weights,
+    //                       bit 24 = last step of its chunk (every (row group, chunk) pair has
+    //                       at least one step; an empty pair gets a step with no weights)
     //   then G x 256 dwords: weight fragment of stripe j in MFMA operand order (lane-major,
     //                       8 16-bit values per lane), all zero when the step has no weight there
     std::vector<uint32_t> stream;
@@ -50,7 +52,7 @@ struct StripeLayout {
 };
 
 struct StripeLayoutDev {
-    int32_t *seg_ptr = nullptr;
+    int32_t *rg_ptr = nullptr;
     int32_t *rg_order = nullptr;
     uint32_t *stream = nullptr;
 };

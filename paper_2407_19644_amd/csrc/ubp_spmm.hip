@@ -138,16 +138,17 @@ __global__ __launch_bounds__(256) void wros_kernel(const int32_t *__restrict__ i
 
 // ------------------------------------------------------------------ MFMA stripe kernel
 struct StripeArgs {
-    const int32_t *seg_ptr;
+    const int32_t *rg_ptr;
     const int32_t *rg_order;
     const uint32_t *stream;
     const uint16_t *X;
     void *Y;
     int64_t ldx, ldy;
     int M, K, N;
-    int nrg, nch, kc; // row groups, chunks, X rows per chunk
-    int n_coltiles, n_wgrows;
-    int vec_ok; // X and Y allow 16-byte vector access on every row
+    int nrg, nch, kc;         // row groups, chunks, X rows per chunk
+    int ctile0, n_coltiles;   // first column tile of this launch, number of tiles in it
+    int n_wgrows;
+    int vec_ok;               // X and Y allow 16-byte vector access on every row
 };
 
 template <bool BF16>
@@ -171,6 +172,20 @@ template <int CT> __device__ __forceinline__ int swz(int row) {
     else return row & 3;
 }
 
+// 16 bytes per lane from global memory straight into LDS at lds_base + 16 * lane (lds_base
+// wave-uniform).  Written as inline assembly on purpose: the compiler then does not treat
+// the load as a pending LDS write, which would make it wait for ALL outstanding vector
+// memory operations before every LDS read and serialise the prefetch pipeline.  Ordering
+// against the LDS reads of the staged data is done by hand (wait_vmcnt + workgroup barrier).
+__device__ __forceinline__ void load16_to_lds(const void *gsrc, uint32_t lds_base) {
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gsrc), "s"(lds_base));
+}
+
+__device__ __forceinline__ uint32_t lds_address(const char *p) {
+    typedef __attribute__((address_space(3))) const char *lds_ptr;
+    return (uint32_t)(uintptr_t)(lds_ptr)p;
+}
+
 template <int N> __device__ __forceinline__ void wait_vmcnt() {
     static_assert(N >= 0 && N < 64, "vmcnt immediate out of range");
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
@@ -184,16 +199,18 @@ constexpr int stripe_max_threads(int G, int CT, int D) {
 // One workgroup = `waves` wavefronts that share one tile of 16*CT columns of X / Y; each
 // wavefront owns one row group (G aligned 16-row stripes) and keeps its G*CT output tiles
 // in fp32 accumulators for the whole K loop (output stationary).
-//  * X is staged chunk by chunk in a double-buffered LDS region with direct global->LDS
-//    loads issued one chunk ahead.
+//  * X is staged chunk by chunk in LDS.  FAST (full column tile, 16-byte aligned rows):
+//    double-buffered, direct global->LDS loads issued one chunk ahead.  Otherwise (ragged
+//    last column tile, odd pitches): through registers, one buffer, zero-filled past N.
 //  * The wavefront's steps form one contiguous stream of fixed-size records (gather rows +
 //    weight fragments); records are fetched D steps ahead into a register ring, so the
-//    stream's memory latency is off the critical path.
+//    stream's memory latency is off the critical path.  A flag in the record marks the
+//    last step of a chunk.
 //  * A step gathers 32 staged rows with two transposed LDS reads per lane and column tile
 //    and issues one 16x16x32 MFMA per (stripe with nonzero weights, column tile).  The
 //    product is formed transposed (pixels x rows) so that a lane holds 4 consecutive
 //    pixels of one output row.
-template <bool BF16, typename TY, int G, int CT, int D>
+template <bool BF16, typename TY, int G, int CT, int D, bool FAST>
 __global__ __launch_bounds__(stripe_max_threads(G, CT, D)) void stripe_kernel(StripeArgs a) {
     constexpr int NTW = 16 * CT;   // columns per workgroup
     constexpr int PITCH = NTW * 2; // bytes per staged row
@@ -207,7 +224,7 @@ __global__ __launch_bounds__(stripe_max_threads(G, CT, D)) void stripe_kernel(St
     const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
     const int my_tiles = (a.n_coltiles - xcd + 7) >> 3;
     if (local >= my_tiles * a.n_wgrows) return;
-    const int ctile = xcd + 8 * (local / a.n_wgrows);
+    const int ctile = a.ctile0 + xcd + 8 * (local / a.n_wgrows);
     const int wgrow = local % a.n_wgrows;
 
     const int nthreads = blockDim.x;
@@ -218,9 +235,6 @@ __global__ __launch_bounds__(stripe_max_threads(G, CT, D)) void stripe_kernel(St
     const int rgi = wgrow * waves + wave;
     const int rg = rgi < a.nrg ? a.rg_order[rgi] : -1;
     const int buf_bytes = a.kc * PITCH;
-    // full tiles with aligned rows are staged with asynchronous direct-to-LDS loads; a ragged
-    // last column tile or unaligned pitches go through registers, synchronously
-    const bool fast = a.vec_ok && (col0 + NTW <= a.N);
 
     float4v acc[G][CT];
 #pragma unroll
@@ -230,8 +244,7 @@ __global__ __launch_bounds__(stripe_max_threads(G, CT, D)) void stripe_kernel(St
 
     // ---- staging of chunk ch into buffer `buf`
     auto stage_async = [&](int ch, char *buf) {
-        typedef __attribute__((address_space(3))) void *lptr;
-        typedef __attribute__((address_space(1))) const void *gptr;
+        const uint32_t lds0 = __builtin_amdgcn_readfirstlane(lds_address(buf));
         const int k0 = ch * a.kc;
         const int rows = min(a.kc, a.K - k0);
         const int ninst = (rows * PIECES + 63) >> 6; // each instruction fills 1 KB of LDS
@@ -241,7 +254,7 @@ __global__ __launch_bounds__(stripe_max_threads(G, CT, D)) void stripe_kernel(St
             if (r < rows) {
                 const int u = (pp >> 1) ^ swz<CT>(r); // logical unit stored at this position
                 const uint16_t *src = a.X + (int64_t)(k0 + r) * a.ldx + col0 + u * 16 + (pp & 1) * 8;
-                __builtin_amdgcn_global_load_lds((gptr)src, (lptr)(buf + i * 1024), 16, 0, 0);
+                load16_to_lds(src, lds0 + (uint32_t)i * 1024u);
             }
         }
     };
@@ -267,9 +280,8 @@ __global__ __launch_bounds__(stripe_max_threads(G, CT, D)) void stripe_kernel(St
     };
 
     // ---- this wavefront's step stream (contiguous over all chunks) and its register ring
-    const int seg0 = rg >= 0 ? rg * a.nch : 0;
-    int s = rg >= 0 ? a.seg_ptr[seg0] : 0;
-    const int s_all = rg >= 0 ? a.seg_ptr[seg0 + a.nch] : 0;
+    int s = rg >= 0 ? a.rg_ptr[rg] : 0;
+    const int s_all = rg >= 0 ? a.rg_ptr[rg + 1] : 0;
     uint32_t info[D];
     uint4 wf[D][G];
     auto issue = [&](int d, int step) {
@@ -279,16 +291,22 @@ __global__ __launch_bounds__(stripe_max_threads(G, CT, D)) void stripe_kernel(St
 #pragma unroll
         for (int j = 0; j < G; ++j) wf[d][j] = fr[j * 64];
     };
+    if (s < s_all) {
+        // same issue order as in the loop (slot by slot), so that the compiler's count of
+        // loads in flight behind each slot is the same on entry and on the back edge
 #pragma unroll
-    for (int d = 0; d < D; ++d)
-        if (s + d < s_all) issue(d, s + d);
+        for (int d = 0; d < D; ++d) {
+            issue(d, min(s + d, s_all - 1));
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
 
-    int ch = -1, s_end = s, since_stage = 0;
+    int ch = -1, since_stage = 0;
     const char *cur = smem;
-    if (fast) stage_async(0, smem);
+    if constexpr (FAST) stage_async(0, smem);
     auto advance = [&]() { // make chunk ch+1 the current one
         ++ch;
-        if (fast) {
+        if constexpr (FAST) {
             // the staging loads of this chunk were issued before the last `since_stage` record
             // fetches; vector memory operations complete in order, so once at most D records
             // (1 + G loads each) are outstanding the staged chunk has landed
@@ -303,46 +321,53 @@ __global__ __launch_bounds__(stripe_max_threads(G, CT, D)) void stripe_kernel(St
             stage_sync(ch, smem);
             __syncthreads();
         }
-        s_end = rg >= 0 ? a.seg_ptr[seg0 + ch + 1] : 0;
     };
+    advance();
 
     const int lane_sub = (lane & 3) * 8; // byte offset of this lane's 4 pixels inside a 32-byte unit
-    bool done = false;
-    while (!done) {
+    // Every step refills its ring slot unconditionally (past the end of the stream the last
+    // record is fetched again and never used): the number of loads in flight behind a slot
+    // is then the same on every path, which lets the compiler wait with a partial vmcnt
+    // instead of draining the ring.
+    if (s < s_all) {
+        const int s_last = s_all - 1;
+        for (;;) {
 #pragma unroll
-        for (int d = 0; d < D; ++d) {
-            while (s >= s_end && ch + 1 < a.nch) advance();
-            if (s >= s_all) {
-                done = true;
-                break;
-            }
-            const uint32_t inf = info[d];
-            const int r_lo = (int)(inf & 0x3ffu), r_hi = (int)((inf >> 10) & 0x3ffu);
-            const uint32_t mask = __builtin_amdgcn_readfirstlane(inf >> 20);
-            const int b_lo = r_lo * PITCH + lane_sub, b_hi = r_hi * PITCH + lane_sub;
-            const int x_lo = swz<CT>(r_lo) << 5, x_hi = swz<CT>(r_hi) << 5;
-            short8v xf[CT];
+            for (int d = 0; d < D; ++d) {
+                const uint32_t inf = info[d];
+                const int r_lo = (int)(inf & 0x3ffu), r_hi = (int)((inf >> 10) & 0x3ffu);
+                const uint32_t flags = __builtin_amdgcn_readfirstlane(inf >> 20);
+                if (flags & 0xfu) {
+                    const int b_lo = r_lo * PITCH + lane_sub, b_hi = r_hi * PITCH + lane_sub;
+                    const int x_lo = swz<CT>(r_lo) << 5, x_hi = swz<CT>(r_hi) << 5;
+                    short8v xf[CT];
 #pragma unroll
-            for (int c = 0; c < CT; ++c) {
-                const short4v p0 = lds_read_tr(cur, b_lo + ((c << 5) ^ x_lo));
-                const short4v p1 = lds_read_tr(cur, b_hi + ((c << 5) ^ x_hi));
-                xf[c] = __builtin_shufflevector(p0, p1, 0, 1, 2, 3, 4, 5, 6, 7);
-            }
+                    for (int c = 0; c < CT; ++c) {
+                        const short4v p0 = lds_read_tr(cur, b_lo + ((c << 5) ^ x_lo));
+                        const short4v p1 = lds_read_tr(cur, b_hi + ((c << 5) ^ x_hi));
+                        xf[c] = __builtin_shufflevector(p0, p1, 0, 1, 2, 3, 4, 5, 6, 7);
+                    }
 #pragma unroll
-            for (int j = 0; j < G; ++j) {
-                if (G == 1 || (mask & (1u << j))) {
-                    const short8v wv = __builtin_bit_cast(short8v, wf[d][j]);
+                    for (int j = 0; j < G; ++j) {
+                        if (G == 1 || (flags & (1u << j))) {
+                            const short8v wv = __builtin_bit_cast(short8v, wf[d][j]);
 #pragma unroll
-                    for (int c = 0; c < CT; ++c) acc[j][c] = mfma16<BF16>(xf[c], wv, acc[j][c]);
+                            for (int c = 0; c < CT; ++c) acc[j][c] = mfma16<BF16>(xf[c], wv, acc[j][c]);
+                        }
+                    }
                 }
-            }
-            if (s + D < s_all) {
-                issue(d, s + D);
+                issue(d, min(s + D, s_last));
                 ++since_stage;
+                if (s == s_last) goto stream_done;
+                ++s;
+                if ((flags & 0x10u) && ch + 1 < a.nch) advance();
             }
-            ++s;
         }
     }
+stream_done:
+    // wavefronts without a row group still take part in every chunk's barriers
+    if (rg < 0)
+        while (ch + 1 < a.nch) advance();
 
     // ---- store: lane (g = lane/16, n = lane%16) holds pixels col0 + 16*c + 4*g + v of row
     // 16*(G*rg + j) + n.  Rows no block touches are stored as zeros like any other.
@@ -403,24 +428,38 @@ ubp_status launch_wros(const ubp_packed *p, const void *X, int64_t ldx, int N, v
 
 constexpr int kPrefetchDepth = 4;
 
-template <bool BF16, typename TY, int G, int CT>
-ubp_status launch_stripe_inst(const StripeArgs &a, int waves, hipStream_t st) {
+template <bool BF16, typename TY, int G, int CT, bool FAST>
+ubp_status launch_stripe_one(StripeArgs a, int ctile0, int n_coltiles, int waves, hipStream_t st) {
     constexpr int D = kPrefetchDepth;
-    if (waves * 64 > stripe_max_threads(G, CT, D)) return UBP_ERR_UNSUPPORTED;
-    // two chunk buffers when there is more than one chunk
-    const size_t lds = (size_t)a.kc * (32 * CT) * (a.nch > 1 ? 2 : 1);
+    // FAST: two chunk buffers when there is more than one chunk
+    const size_t lds = (size_t)a.kc * (32 * CT) * ((FAST && a.nch > 1) ? 2 : 1);
     static size_t attr_bytes = 0; // per instantiation; the limit is only ever raised
     if (lds > attr_bytes) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&stripe_kernel<BF16, TY, G, CT, D>),
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&stripe_kernel<BF16, TY, G, CT, D, FAST>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
             (void)hipGetLastError();
             return UBP_ERR_DEVICE;
         }
         attr_bytes = lds;
     }
-    const unsigned grid = 8u * (unsigned)((a.n_coltiles + 7) / 8) * (unsigned)a.n_wgrows;
-    hipLaunchKernelGGL((stripe_kernel<BF16, TY, G, CT, D>), dim3(grid), dim3((unsigned)waves * 64), lds, st, a);
+    a.ctile0 = ctile0;
+    a.n_coltiles = n_coltiles;
+    const unsigned grid = 8u * (unsigned)((n_coltiles + 7) / 8) * (unsigned)a.n_wgrows;
+    hipLaunchKernelGGL((stripe_kernel<BF16, TY, G, CT, D, FAST>), dim3(grid), dim3((unsigned)waves * 64), lds, st, a);
     return hipGetLastError() == hipSuccess ? UBP_OK : UBP_ERR_DEVICE;
+}
+
+template <bool BF16, typename TY, int G, int CT>
+ubp_status launch_stripe_inst(const StripeArgs &a, int waves, hipStream_t st) {
+    if (waves * 64 > stripe_max_threads(G, CT, kPrefetchDepth)) return UBP_ERR_UNSUPPORTED;
+    // full column tiles with aligned rows take the asynchronous staging path; a ragged last
+    // tile (or everything, when rows are not 16-byte aligned) takes the synchronous one
+    const int total = (a.N + 16 * CT - 1) / (16 * CT);
+    const int full = a.vec_ok ? a.N / (16 * CT) : 0;
+    ubp_status rc = UBP_OK;
+    if (full > 0) rc = launch_stripe_one<BF16, TY, G, CT, true>(a, 0, full, waves, st);
+    if (rc == UBP_OK && total > full) rc = launch_stripe_one<BF16, TY, G, CT, false>(a, full, total - full, waves, st);
+    return rc;
 }
 
 template <bool BF16, typename TY>
@@ -483,7 +522,7 @@ ubp_status upload(ubp_packed *p) {
         for (int s = 0; s < kNumLayouts && ok; ++s) {
             const StripeLayout &L = p->sg[s];
             StripeLayoutDev &D = p->d_sg[s];
-            ok = ok && dev_copy(&D.seg_ptr, L.seg_ptr.data(), L.seg_ptr.size(), &p->device_bytes);
+            ok = ok && dev_copy(&D.rg_ptr, L.rg_ptr.data(), L.rg_ptr.size(), &p->device_bytes);
             ok = ok && dev_copy(&D.rg_order, L.rg_order.data(), L.rg_order.size(), &p->device_bytes);
             ok = ok && dev_copy(&D.stream, L.stream.data(), L.stream.size(), &p->device_bytes);
         }
@@ -507,7 +546,7 @@ void release_device(ubp_packed *p) {
     rel(p->d_indices);
     rel(p->d_values_f32);
     for (int s = 0; s < kNumLayouts; ++s) {
-        rel(p->d_sg[s].seg_ptr);
+        rel(p->d_sg[s].rg_ptr);
         rel(p->d_sg[s].rg_order);
         rel(p->d_sg[s].stream);
     }
@@ -591,7 +630,7 @@ ubp_status ubp_spmm_plan(const ubp_packed *p, const void *X_dev, int64_t ldx, in
     if (waves < 1 || waves > max_waves) return UBP_ERR_UNSUPPORTED;
 
     StripeArgs a;
-    a.seg_ptr = p->d_sg[slot].seg_ptr;
+    a.rg_ptr = p->d_sg[slot].rg_ptr;
     a.rg_order = p->d_sg[slot].rg_order;
     a.stream = p->d_sg[slot].stream;
     a.X = static_cast<const uint16_t *>(X_dev);
@@ -604,7 +643,8 @@ ubp_status ubp_spmm_plan(const ubp_packed *p, const void *X_dev, int64_t ldx, in
     a.nrg = L.nrg;
     a.nch = L.nch;
     a.kc = L.chunk_rows;
-    a.n_coltiles = (N + 16 * CT - 1) / (16 * CT);
+    a.ctile0 = 0;
+    a.n_coltiles = 0;
     a.n_wgrows = (L.nrg + waves - 1) / waves;
     const size_t ysz = (y_dtype == UBP_F32) ? 4 : 2;
     a.vec_ok = (ldx % 8 == 0) && (reinterpret_cast<uintptr_t>(X_dev) % 16 == 0) && ((ldy * ysz) % 16 == 0) &&
