@@ -129,17 +129,25 @@ ubp_status ubp_spmm(const ubp_packed *p, const void *X_dev, int64_t ldx, int32_t
  *                dtype, bh <= 16); 2 = MFMA kernel on aligned 16-row stripes (f16 / bf16).
  *   sub_stripes: MFMA kernel, 16-row stripes per wavefront (1, 2 or 4).
  *   col_tiles  : MFMA kernel, 16-column tiles per wavefront (2, 4 or 8).
- *   waves      : wavefronts per workgroup (1..16).
+ *   waves      : wavefronts per workgroup (MFMA kernel: 2..16, one of them stages X).
  *   rows_per_range : WROS kernel, output rows owned by one workgroup row (multiple of bh).
- *   chunk_rows : MFMA kernel, rows of X staged in LDS at a time (256, 512 or 1024).
  */
 typedef struct {
-    int32_t kernel, sub_stripes, col_tiles, waves, rows_per_range, chunk_rows, reserved[2];
+    int32_t kernel, sub_stripes, col_tiles, waves, rows_per_range, reserved[3];
 } ubp_plan;
 
 ubp_status ubp_spmm_plan(const ubp_packed *p, const void *X_dev, int64_t ldx, int32_t N,
                          void *Y_dev, int64_t ldy, ubp_dtype y_dtype, void *hip_stream,
                          const ubp_plan *plan);
+
+/*
+ * Synchronous health check (copies one word from the device, so it waits for the work queued
+ * before it on the NULL stream's terms; call it after synchronising the stream you used).
+ * Every wait inside the MFMA kernel is bounded; a wait that runs out sets a bit here and the
+ * kernel finishes with undefined Y instead of hanging.  *flags == 0 means no such event since
+ * the handle was packed.
+ */
+ubp_status ubp_packed_device_error(const ubp_packed *p, uint32_t *flags);
 
 /*
  * Facts about a handle, for reporting.  what: 0 M, 1 K, 2 bh, 3 bw, 4 nb, 5 dtype,

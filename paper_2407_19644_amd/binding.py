@@ -17,7 +17,7 @@ DTYPES = {"f32": 0, "f16": 1, "bf16": 2}
 _NP_OF = {"f32": np.float32, "f16": np.float16, "bf16": np.uint16}
 EXPORTS = ("ubp_target_block_count", "ubp_select_reference", "ubp_pack", "ubp_packed_indptr",
            "ubp_packed_indices", "ubp_packed_values", "ubp_spmm", "ubp_spmm_plan", "ubp_packed_info",
-           "ubp_packed_free", "ubp_status_string")
+           "ubp_packed_free", "ubp_status_string", "ubp_packed_device_error")
 
 
 class UBPError(RuntimeError):
@@ -29,8 +29,7 @@ class UBPError(RuntimeError):
 class Plan(ctypes.Structure):
     """Mirror of ubp_plan; zero fields mean 'choose automatically'."""
     _fields_ = [("kernel", ctypes.c_int32), ("sub_stripes", ctypes.c_int32), ("col_tiles", ctypes.c_int32),
-                ("waves", ctypes.c_int32), ("rows_per_range", ctypes.c_int32), ("chunk_rows", ctypes.c_int32),
-                ("reserved", ctypes.c_int32 * 2)]
+                ("waves", ctypes.c_int32), ("rows_per_range", ctypes.c_int32), ("reserved", ctypes.c_int32 * 3)]
 
 
 _lib = None
@@ -65,6 +64,8 @@ def load_library():
     L.ubp_spmm_plan.restype = ctypes.c_int
     L.ubp_packed_info.argtypes = [vp, i32]
     L.ubp_packed_info.restype = i64
+    L.ubp_packed_device_error.argtypes = [vp, ctypes.POINTER(ctypes.c_uint32)]
+    L.ubp_packed_device_error.restype = ctypes.c_int
     L.ubp_packed_free.argtypes = [vp]
     L.ubp_packed_free.restype = None
     L.ubp_status_string.argtypes = [ctypes.c_int]
@@ -131,6 +132,14 @@ class Packed:
     @property
     def values(self):
         return self._view(load_library().ubp_packed_values, _NP_OF[self.dtype])
+
+    def device_error(self):
+        """Flags raised by a kernel whose bounded wait ran out (0 = healthy)."""
+        flags = ctypes.c_uint32(0)
+        rc = load_library().ubp_packed_device_error(self.handle, ctypes.byref(flags))
+        if rc != UBP_OK:
+            raise UBPError(rc, "ubp_packed_device_error")
+        return int(flags.value)
 
     def free(self):
         if self._h:

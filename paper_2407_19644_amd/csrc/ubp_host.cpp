@@ -270,6 +270,7 @@ int64_t ubp_packed_info(const ubp_packed *p, int32_t what) {
     default:
         // 100 + layout slot: weight fragments (MFMA issues per 16-column tile) of that layout
         if (what >= 100 && what < 100 + ubp::kNumLayouts) return p->sg[what - 100].total_mfma;
+        if (what >= 200 && what < 200 + ubp::kNumLayouts) return p->sg[what - 200].nsteps;
         return -1;
     }
 }
@@ -309,24 +310,27 @@ struct Entry {
 
 } // namespace
 
-static void build_one(ubp_packed *p, StripeLayout &L, int G, int kChunkRows) {
+static void build_one(ubp_packed *p, StripeLayout &L, int G, int CT) {
     const int M = p->M, K = p->K, bh = p->bh, bw = p->bw;
     const int rgh = kStripe * G;
+    const int RR = ring_rows(CT), PITCH = ring_pitch(CT), R = ring_slots(CT);
     L.G = G;
-    L.chunk_rows = kChunkRows;
+    L.CT = CT;
     L.nrg = (M + rgh - 1) / rgh;
-    L.nch = (K + kChunkRows - 1) / kChunkRows;
+    L.nch = (K + kSlotRows - 1) / kSlotRows;
     L.rg_ptr.assign((size_t)L.nrg + 1, 0);
     L.stream.clear();
     L.nsteps = 0;
-    const size_t rec_dw = 64 + 256 * (size_t)G;
     L.total_mfma = 0;
+    const size_t rec_dw = 128 + 256 * (size_t)G;
     const uint16_t *vals = reinterpret_cast<const uint16_t *>(p->values.data());
     const int32_t nstart = M - bh + 1; // start rows 0..M-bh
     std::vector<int32_t> colslot((size_t)K, -1);
     std::vector<Entry> entries;
     std::vector<uint16_t> wbuf; // [entry slot][rgh]
     std::vector<int64_t> rg_weight((size_t)L.nrg, 0);
+    struct Step { size_t pos, n; int cmin, cmax, rel; };
+    std::vector<Step> steps;
 
     for (int rg = 0; rg < L.nrg; ++rg) {
         const int row0 = rg * rgh, row1 = std::min(M, row0 + rgh);
@@ -354,59 +358,78 @@ static void build_one(ubp_packed *p, StripeLayout &L, int G, int kChunkRows) {
             }
         }
         for (const Entry &e : entries) colslot[(size_t)e.k] = -1;
-        std::sort(entries.begin(), entries.end(), [kChunkRows](const Entry &a, const Entry &b) {
-            const int ca = a.k / kChunkRows, cb = b.k / kChunkRows;
-            if (ca != cb) return ca < cb;
+        std::sort(entries.begin(), entries.end(), [](const Entry &a, const Entry &b) {
+            const int wa = a.k / kWindow, wb = b.k / kWindow;
+            if (wa != wb) return wa < wb;
             if (a.mask != b.mask) return a.mask < b.mask;
             return a.k < b.k;
         });
-        size_t pos = 0;
+        // steps: up to 32 entries whose X rows lie in at most R-1 consecutive ring slots, so
+        // that they can be resident together with one slot to spare for the producer
+        steps.clear();
+        for (size_t pos = 0; pos < entries.size();) {
+            int cmin = entries[pos].k / kSlotRows, cmax = cmin;
+            size_t n = 0;
+            while (n < (size_t)kStep && pos + n < entries.size()) {
+                const int c = entries[pos + n].k / kSlotRows;
+                const int lo = std::min(cmin, c), hi = std::max(cmax, c);
+                if (hi - lo > R - 2) break;
+                cmin = lo;
+                cmax = hi;
+                ++n;
+            }
+            steps.push_back(Step{pos, n, cmin, cmax, 0});
+            pos += n;
+        }
+        for (size_t s = steps.size(), m = (size_t)L.nch; s-- > 0;) {
+            m = std::min<size_t>(m, (size_t)steps[s].cmin);
+            steps[s].rel = (int)m; // chunks below this are never read by this or any later step
+            // a consumer holds chunks rel..cmax at this step; they must fit the ring with a slot
+            // to spare or producer and consumer could wait for each other
+            if (steps[s].cmax - steps[s].rel > R - 2) {
+                L.G = 0; // unusable; the launcher reports UBP_ERR_UNSUPPORTED
+                return;
+            }
+        }
         L.rg_ptr[(size_t)rg] = (int32_t)L.nsteps;
-        for (int ch = 0; ch < L.nch; ++ch) {
-            size_t end = pos;
-            while (end < entries.size() && entries[end].k / kChunkRows == ch) ++end;
-            if (end == pos) { // no weights in this chunk: one step that only carries the chunk-end flag
-                L.stream.resize(L.stream.size() + rec_dw, 0u);
-                for (int lane = 0; lane < 64; ++lane) L.stream[L.stream.size() - rec_dw + lane] = 1u << 24;
-                ++L.nsteps;
+        for (const Step &st : steps) {
+            uint32_t mask = 0;
+            for (size_t e = 0; e < st.n; ++e) mask |= entries[st.pos + e].mask;
+            const size_t rec = L.stream.size();
+            L.stream.resize(rec + rec_dw, 0u);
+            // ring row of entry idx of this step; padding entries repeat the first row
+            auto ring_row = [&](size_t idx) { return (idx < st.n ? entries[st.pos + idx].k : entries[st.pos].k) % RR; };
+            auto lds_addr = [&](size_t idx, int sub) {
+                const int r = ring_row(idx);
+                return (uint32_t)(r * PITCH + (ring_swizzle(CT, r) << 5) + sub);
+            };
+            const uint32_t ctl = (uint32_t)st.cmax | ((uint32_t)st.rel << 16);
+            for (int lane = 0; lane < 64; ++lane) {
+                // lanes 4e..4e+3 of 16-lane group g read entry 4g+e (first transposed read) and
+                // entry 16+4g+e (second); each of the 4 lanes reads 8 bytes (4 pixels)
+                const int g = lane / 16, t = lane % 16, e = t / 4, sub = (t % 4) * 8;
+                const uint32_t lo = lds_addr((size_t)(4 * g + e), sub), hi = lds_addr((size_t)(16 + 4 * g + e), sub);
+                L.stream[rec + 2 * lane] = (lo >> 3) | ((hi >> 3) << 14) | (mask << 28);
+                L.stream[rec + 2 * lane + 1] = ctl;
             }
-            for (size_t s = pos; s < end; s += kStep) {
-                const size_t n = std::min<size_t>(kStep, end - s);
-                uint32_t mask = 0;
-                for (size_t e = 0; e < n; ++e) mask |= entries[s + e].mask;
-                const size_t rec = L.stream.size();
-                L.stream.resize(rec + rec_dw, 0u);
-                // X rows gathered by this step, chunk-relative; padding repeats the first row
-                int32_t rows[kStep];
-                for (size_t e = 0; e < (size_t)kStep; ++e)
-                    rows[e] = (e < n ? entries[s + e].k : entries[s].k) - ch * kChunkRows;
-                // a lane's two transposed reads fetch entries 8g + t/4 and 8g + 4 + t/4 (t = lane mod 16)
+            // weight fragments: lane (n = lane mod 16, g = lane / 16) holds row 16*j + n and, in
+            // element order, entries 4g..4g+3 then 16+4g..16+4g+3 (the order the reads deliver)
+            uint16_t *frag = reinterpret_cast<uint16_t *>(&L.stream[rec + 128]);
+            for (int j = 0; j < G; ++j) {
+                if (!(mask & (1u << j))) continue;
                 for (int lane = 0; lane < 64; ++lane) {
-                    const int g = lane / 16, t = lane % 16;
-                    const uint32_t lo = (uint32_t)rows[8 * g + t / 4], hi = (uint32_t)rows[8 * g + 4 + t / 4];
-                    const uint32_t last = (s + kStep >= end) ? (1u << 24) : 0u;
-                    L.stream[rec + lane] = lo | (hi << 10) | (mask << 20) | last;
-                }
-                // weight fragments: lane (n = lane mod 16, g = lane / 16) holds row 16*j + n,
-                // entries 8g .. 8g+7
-                uint16_t *frag = reinterpret_cast<uint16_t *>(&L.stream[rec + 64]);
-                for (int j = 0; j < G; ++j) {
-                    if (!(mask & (1u << j))) continue;
-                    for (int lane = 0; lane < 64; ++lane) {
-                        const int g = lane / 16, nrow = lane % 16;
-                        for (int e = 0; e < 8; ++e) {
-                            const size_t idx = (size_t)(8 * g + e);
-                            if (idx < n)
-                                frag[((size_t)j * 64 + lane) * 8 + e] =
-                                    wbuf[(size_t)entries[s + idx].slot * rgh + (kStripe * j + nrow)];
-                        }
+                    const int g = lane / 16, nrow = lane % 16;
+                    for (int e = 0; e < 8; ++e) {
+                        const size_t idx = (size_t)(e < 4 ? 4 * g + e : 16 + 4 * g + (e - 4));
+                        if (idx < st.n)
+                            frag[((size_t)j * 64 + lane) * 8 + e] =
+                                wbuf[(size_t)entries[st.pos + idx].slot * rgh + (kStripe * j + nrow)];
                     }
-                    ++L.total_mfma;
-                    ++rg_weight[(size_t)rg];
                 }
-                ++L.nsteps;
+                ++L.total_mfma;
+                ++rg_weight[(size_t)rg];
             }
-            pos = end;
+            ++L.nsteps;
         }
     }
     L.rg_ptr[(size_t)L.nrg] = (int32_t)L.nsteps;
@@ -417,7 +440,8 @@ static void build_one(ubp_packed *p, StripeLayout &L, int G, int kChunkRows) {
 }
 
 void build_stripe_layouts(ubp_packed *p) {
-    for (int s = 0; s < kNumLayouts; ++s) build_one(p, p->sg[s], slot_G(s), slot_KC(s));
+    if ((p->K + kSlotRows - 1) / kSlotRows > 0xffff) return; // chunk indices are 16-bit in the records
+    for (int s = 0; s < kNumLayouts; ++s) build_one(p, p->sg[s], slot_G(s), slot_CT(s));
 }
 
 } // namespace ubp

@@ -8,47 +8,62 @@
 
 namespace ubp {
 
-constexpr int kStripe = 16;     // rows of one MFMA output tile (aligned row stripe)
-constexpr int kStep = 32;       // gathered X rows consumed by one 16x16x32 MFMA
-constexpr int kNumG = 3;        // stripes per wavefront: 1, 2, 4
-constexpr int kNumKC = 3;       // X rows staged in LDS per chunk: 256, 512, 1024
-constexpr int kNumLayouts = kNumG * kNumKC;
+constexpr int kStripe = 16;    // rows of one MFMA output tile (aligned row stripe)
+constexpr int kStep = 32;      // gathered X rows consumed by one 16x16x32 MFMA
+constexpr int kSlotRows = 64;  // X rows per slot of the LDS ring (the unit the producer stages)
+constexpr int kWindow = 128;   // entries are grouped by stripe set inside windows of this many X rows
+constexpr int kNumG = 3;       // stripes per wavefront: 1, 2, 4
+constexpr int kNumCT = 3;      // 16-column tiles per wavefront: 2, 4, 8
+constexpr int kNumLayouts = kNumG * kNumCT;
 
-// A layout is built for every (G, chunk rows) pair the launcher can choose.
-inline int layout_slot(int G, int KC) {
+// A layout is built for every (G, CT) the kernel is instantiated for; CT fixes the byte
+// addresses inside the LDS ring that the records carry.
+inline int layout_slot(int G, int CT) {
     const int gi = G == 1 ? 0 : G == 2 ? 1 : G == 4 ? 2 : -1;
-    const int ki = KC == 256 ? 0 : KC == 512 ? 1 : KC == 1024 ? 2 : -1;
-    return (gi < 0 || ki < 0) ? -1 : gi * kNumKC + ki;
+    const int ci = CT == 2 ? 0 : CT == 4 ? 1 : CT == 8 ? 2 : -1;
+    return (gi < 0 || ci < 0) ? -1 : gi * kNumCT + ci;
 }
-inline int slot_G(int slot) { return 1 << (slot / kNumKC); }
-inline int slot_KC(int slot) { return 256 << (slot % kNumKC); }
+inline int slot_G(int slot) { return 1 << (slot / kNumCT); }
+inline int slot_CT(int slot) { return 2 << (slot % kNumCT); }
 
-// Host image of the MFMA kernel's private re-layout of the packed weights, for one
-// choice of G (16-row stripes handled together by one wavefront).
+// LDS ring geometry for a column-tile width: rows of 32*CT bytes, 64 KB (CT = 2, 4) or
+// 128 KB (CT = 8), always a power-of-two number of rows so that ring row = X row mod rows.
+constexpr int ring_pitch(int CT) { return 32 * CT; }
+constexpr int ring_rows(int CT) { return CT == 2 ? 1024 : 512; }
+constexpr int ring_slots(int CT) { return ring_rows(CT) / kSlotRows; }
+
+// Position of the 32-byte unit u (16 pixels) inside ring row r is u ^ ring_swizzle(r): LDS
+// has 64 four-byte banks, and this spreads 16 consecutive rows of one unit over all of them.
+constexpr int ring_swizzle(int CT, int r) { return CT == 2 ? ((r >> 2) & 1) : CT == 4 ? ((r >> 1) & 3) : (r & 7); }
+
+// Host image of the MFMA kernel's private re-layout of the packed weights, for one (G, CT).
 //
 // Rows are cut into row groups of 16*G aligned rows.  For a row group the columns of W
 // that hold at least one kept weight in it are its "entries"; an entry is one row of X
 // to gather plus the 16*G weights of that column (zero where no block covers the row).
-// Entries are cut by chunk of chunk_rows X rows, ordered inside a chunk by the set of
-// stripes they touch and then by column, and grouped 32 at a time into "steps".
+// Entries are ordered by window of kWindow X rows, inside a window by the set of stripes
+// they touch and then by column, and grouped 32 at a time into "steps" whose rows fit the
+// LDS ring together.
 struct StripeLayout {
-    int G = 0;
-    int chunk_rows = 0; // X rows per LDS chunk
+    int G = 0, CT = 0;
     int nrg = 0;     // row groups
-    int nch = 0;     // chunks of X rows
+    int nch = 0;     // slots (chunks of kSlotRows X rows) the producer stages: ceil(K / 64)
     std::vector<int32_t> rg_ptr;     // [nrg + 1] first step of each row group
     std::vector<int32_t> rg_order;   // row groups, heaviest (most MFMAs) first
-    // One fixed-size record per step, (64 + 256*G) dwords, so that the address of any later
+    // One fixed-size record per step, (128 + 256*G) dwords, so that the address of any later
     // step is known without reading metadata:
-    //   dwords 0..63      : per lane, bits 0-9 / 10-19 = chunk-relative X rows of the lane's two
-    //                       transposed LDS reads, bits 20-23 = stripes with nonzero weights,
-    //                       bit 24 = last step of its chunk (every (row group, chunk) pair has
-    //                       at least one step; an empty pair gets a step with no weights)
+    //   dwords 0..127 : per lane a pair {addr, ctl}
+    //       addr bits 0-13 / 14-27 : LDS byte address >> 3 of the lane's two transposed reads
+    //                                (ring row, swizzle and the lane's 8-byte column included;
+    //                                column tile c is then reached by XOR with c << 5)
+    //       addr bits 28-31        : stripes with nonzero weights in this step
+    //       ctl (same in all lanes): bits 0-15 highest chunk the step reads, bits 16-31 number
+    //                                of leading chunks that no step from here on reads
     //   then G x 256 dwords: weight fragment of stripe j in MFMA operand order (lane-major,
-    //                       8 16-bit values per lane), all zero when the step has no weight there
+    //                        8 16-bit values per lane), all zero when the step has no weight there
     std::vector<uint32_t> stream;
     int64_t nsteps = 0;
-    int64_t total_mfma = 0;          // MFMA issues per 16-column tile (steps x stripes with weights)
+    int64_t total_mfma = 0; // MFMA issues per 16-column tile (steps x stripes with weights)
 };
 
 struct StripeLayoutDev {
@@ -74,6 +89,7 @@ struct ubp_packed {
     int32_t *d_indices = nullptr;
     float *d_values_f32 = nullptr; // rotated values widened to fp32 (exact)
     ubp::StripeLayoutDev d_sg[ubp::kNumLayouts];
+    uint32_t *d_error = nullptr;   // set by a kernel whose bounded wait ran out
     int64_t device_bytes = 0;
 };
 

@@ -145,10 +145,11 @@ struct StripeArgs {
     void *Y;
     int64_t ldx, ldy;
     int M, K, N;
-    int nrg, nch, kc;         // row groups, chunks, X rows per chunk
-    int ctile0, n_coltiles;   // first column tile of this launch, number of tiles in it
+    int nrg, nch;            // row groups, 64-row chunks of X
+    int ctile0, n_coltiles;  // first column tile of this launch, number of tiles in it
     int n_wgrows;
-    int vec_ok;               // X and Y allow 16-byte vector access on every row
+    int vec_ok;              // X and Y allow 16-byte vector access on every row
+    uint32_t *err;           // set to nonzero when a bounded wait runs out
 };
 
 template <bool BF16>
@@ -164,19 +165,11 @@ __device__ __forceinline__ short4v lds_read_tr(const char *lds_base, int byte_of
     return __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(lds_base + byte_off));
 }
 
-// LDS layout of a staged chunk: row pitch = 32*CT bytes (no padding), and the 32-byte unit
-// u (16 pixels) of row r is stored at unit position u ^ swz(r), chosen so that 4
-// consecutive rows put the same logical unit on the 4 different 32-byte bank groups.
-template <int CT> __device__ __forceinline__ int swz(int row) {
-    if constexpr (CT == 2) return (row >> 1) & 1;
-    else return row & 3;
-}
-
 // 16 bytes per lane from global memory straight into LDS at lds_base + 16 * lane (lds_base
 // wave-uniform).  Written as inline assembly on purpose: the compiler then does not treat
 // the load as a pending LDS write, which would make it wait for ALL outstanding vector
-// memory operations before every LDS read and serialise the prefetch pipeline.  Ordering
-// against the LDS reads of the staged data is done by hand (wait_vmcnt + workgroup barrier).
+// memory operations before every LDS read.  Ordering against the LDS reads of the staged
+// data is done by hand (wait_vmcnt, then the slot's ready flag).
 __device__ __forceinline__ void load16_to_lds(const void *gsrc, uint32_t lds_base) {
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gsrc), "s"(lds_base));
 }
@@ -191,32 +184,49 @@ template <int N> __device__ __forceinline__ void wait_vmcnt() {
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
-constexpr int stripe_max_threads(int G, int CT, int D) {
-    // accumulators + operand fragments + D prefetched step records, in VGPRs per lane
-    return (4 * G * CT + 4 * CT + D * (1 + 4 * G) + 24) <= 128 ? 1024 : 512;
+__device__ __forceinline__ uint32_t flag_load(uint32_t *p) {
+    return __hip_atomic_load(p, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP);
 }
 
-// One workgroup = `waves` wavefronts that share one tile of 16*CT columns of X / Y; each
-// wavefront owns one row group (G aligned 16-row stripes) and keeps its G*CT output tiles
-// in fp32 accumulators for the whole K loop (output stationary).
-//  * X is staged chunk by chunk in LDS.  FAST (full column tile, 16-byte aligned rows):
-//    double-buffered, direct global->LDS loads issued one chunk ahead.  Otherwise (ragged
-//    last column tile, odd pitches): through registers, one buffer, zero-filled past N.
-//  * The wavefront's steps form one contiguous stream of fixed-size records (gather rows +
-//    weight fragments); records are fetched D steps ahead into a register ring, so the
-//    stream's memory latency is off the critical path.  A flag in the record marks the
-//    last step of a chunk.
+constexpr int kSpinLimit = 1 << 22; // polls before a wait gives up (each poll is >= 100 cycles)
+
+constexpr int stripe_max_threads(int G, int CT, int D) {
+    // accumulators + operand fragments + D prefetched step records, in VGPRs per lane
+    return (4 * G * CT + 4 * CT + D * (2 + 4 * G) + 24) <= 128 ? 1024 : 512;
+}
+
+// One workgroup = one producer wavefront + up to 15 consumer wavefronts sharing one tile of
+// 16*CT columns of X / Y.
+//  * The producer stages X in 64-row chunks into a ring of LDS slots (ring row = X row mod
+//    ring rows).  FAST (full column tile, 16-byte aligned rows): direct global->LDS loads,
+//    several chunks in flight; otherwise (ragged last column tile, odd pitches) through
+//    registers with zero fill past column N.  A chunk's slot is refilled only after every
+//    consumer has released the chunk that occupied it (done counters), and a chunk is read
+//    only after the producer has published it (ready generation numbers); there is no
+//    workgroup barrier after start-up, so consumers drift apart by up to a ring of rows and
+//    their uneven per-chunk work averages out.
+//  * Each consumer owns one row group (G aligned 16-row stripes) and keeps its G*CT output
+//    tiles in fp32 accumulators for the whole K loop (output stationary).  Its steps form a
+//    contiguous stream of fixed-size records (LDS gather addresses, chunk bookkeeping,
+//    weight fragments), fetched D steps ahead into a register ring.
 //  * A step gathers 32 staged rows with two transposed LDS reads per lane and column tile
 //    and issues one 16x16x32 MFMA per (stripe with nonzero weights, column tile).  The
 //    product is formed transposed (pixels x rows) so that a lane holds 4 consecutive
 //    pixels of one output row.
+// Every wait is bounded: if one runs out the wavefront raises *err and goes on without
+// waiting (wrong numbers, but the kernel always terminates).
 template <bool BF16, typename TY, int G, int CT, int D, bool FAST>
 __global__ __launch_bounds__(stripe_max_threads(G, CT, D)) void stripe_kernel(StripeArgs a) {
-    constexpr int NTW = 16 * CT;   // columns per workgroup
-    constexpr int PITCH = NTW * 2; // bytes per staged row
+    constexpr int NTW = 16 * CT;
+    constexpr int PITCH = ring_pitch(CT);
     constexpr int PIECES = 2 * CT; // 16-byte pieces per staged row
-    constexpr int REC_DW = 64 + 256 * G;
+    constexpr int RR = ring_rows(CT), R = ring_slots(CT), KS = kSlotRows;
+    constexpr int REC_DW = 128 + 256 * G;
+    constexpr int NINST = KS * PIECES / 64; // direct-to-LDS instructions per chunk (1 KB each)
+    constexpr int LAG = 32 / NINST;         // chunks kept in flight before their readiness is published
     extern __shared__ __attribute__((aligned(1024))) char smem[];
+    uint32_t *ready = reinterpret_cast<uint32_t *>(smem + RR * PITCH); // [R] generation + 1 of the chunk in the slot
+    uint32_t *done = ready + R;                                        // [R] releases received, all generations
 
     // workgroup -> (column tile, workgroup row); consecutive workgroup ids go round-robin
     // over the 8 XCDs, so tiles are dealt by id mod 8 and all row groups of one column tile
@@ -227,14 +237,101 @@ __global__ __launch_bounds__(stripe_max_threads(G, CT, D)) void stripe_kernel(St
     const int ctile = a.ctile0 + xcd + 8 * (local / a.n_wgrows);
     const int wgrow = local % a.n_wgrows;
 
-    const int nthreads = blockDim.x;
-    const int waves = nthreads >> 6;
+    const int NC = (int)(blockDim.x >> 6) - 1; // consumer wavefronts; the last wavefront produces
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lane = threadIdx.x & 63;
     const int col0 = ctile * NTW;
-    const int rgi = wgrow * waves + wave;
-    const int rg = rgi < a.nrg ? a.rg_order[rgi] : -1;
-    const int buf_bytes = a.kc * PITCH;
+    const int rg0 = wgrow * NC;
+    const int active = min(NC, a.nrg - rg0); // consumers that own a row group
+
+    if (threadIdx.x < 2 * R) ready[threadIdx.x] = 0u; // ready[] and done[]
+    __syncthreads();
+
+    // ------------------------------------------------------------------ producer
+    if (wave == NC) {
+        int published = 0;
+        bool broken = false;
+        auto publish_upto = [&](int upto) {
+            while (published < upto) {
+                // relaxed on purpose: the data is known to have landed (explicit vmcnt wait, or LDS
+                // writes of this same wavefront, which LDS executes in order before this store); a
+                // release here would make the compiler drain every load still in flight
+                if (lane == 0)
+                    __hip_atomic_store(&ready[published % R], (uint32_t)(published / R + 1), __ATOMIC_RELAXED,
+                                       __HIP_MEMORY_SCOPE_WORKGROUP);
+                ++published;
+            }
+        };
+        const uint32_t ring0 = __builtin_amdgcn_readfirstlane(lds_address(smem));
+        const int r_in = lane / PIECES, pp = lane % PIECES;
+        for (int c = 0; c < a.nch; ++c) {
+            const int slot = c % R;
+            if (c >= R && !broken) {
+                const uint32_t target = (uint32_t)active * (uint32_t)(c / R);
+                if (flag_load(&done[slot]) < target) {
+                    // about to block: first publish every chunk already issued, the consumers
+                    // this wait depends on may be waiting for one of them
+                    wait_vmcnt<0>();
+                    publish_upto(c);
+                    int spins = 0;
+                    while (flag_load(&done[slot]) < target) {
+                        if (++spins > kSpinLimit) {
+                            broken = true;
+                            if (lane == 0) atomicOr(a.err, 1u);
+                            break;
+                        }
+                        __builtin_amdgcn_s_sleep(2);
+                    }
+                }
+            }
+            const int k0 = c * KS;
+            const int rows = min(KS, a.K - k0);
+            if constexpr (FAST) {
+                const uint32_t lds0 = ring0 + (uint32_t)(slot * KS * PITCH);
+#pragma unroll
+                for (int i = 0; i < NINST; ++i) {
+                    const int r = i * (64 / PIECES) + r_in;             // row inside the slot
+                    const int u = (pp >> 1) ^ ring_swizzle(CT, slot * KS + r); // logical unit stored at this position
+                    // rows past K load the chunk's last row again (never read): every chunk then
+                    // issues exactly NINST loads, which the in-order vmcnt bookkeeping relies on
+                    const uint16_t *src = a.X + (int64_t)(k0 + min(r, rows - 1)) * a.ldx + col0 + u * 16 + (pp & 1) * 8;
+                    load16_to_lds(src, lds0 + (uint32_t)i * 1024u);
+                }
+                if (c + 1 - published > LAG) {
+                    wait_vmcnt<LAG * NINST>(); // vector memory completes in order: chunks <= c - LAG have landed
+                    publish_upto(c + 1 - LAG);
+                }
+            } else {
+                for (int piece = lane; piece < rows * PIECES; piece += 64) {
+                    const int r = piece / PIECES, q = piece % PIECES;
+                    const int u = (q >> 1) ^ ring_swizzle(CT, slot * KS + r);
+                    const int col = col0 + u * 16 + (q & 1) * 8;
+                    const uint16_t *src = a.X + (int64_t)(k0 + r) * a.ldx + col;
+                    uint4 v;
+                    if (a.vec_ok && col + 8 <= a.N) {
+                        v = *reinterpret_cast<const uint4 *>(src);
+                    } else {
+                        uint32_t e[8];
+#pragma unroll
+                        for (int t = 0; t < 8; ++t) e[t] = (col + t < a.N) ? (uint32_t)src[t] : 0u;
+                        v = uint4{e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16), e[6] | (e[7] << 16)};
+                    }
+                    *reinterpret_cast<uint4 *>(smem + (slot * KS + r) * PITCH + q * 16) = v;
+                }
+                asm volatile("" ::: "memory");
+                publish_upto(c + 1); // LDS executes this wavefront's writes above before the flag store
+            }
+        }
+        wait_vmcnt<0>();
+        publish_upto(a.nch);
+        return;
+    }
+    if (wave >= active) return; // no row group left for this wavefront
+
+    // ------------------------------------------------------------------ consumer
+    const int rg = a.rg_order[rg0 + wave];
+    int s = a.rg_ptr[rg];
+    const int s_all = a.rg_ptr[rg + 1];
 
     float4v acc[G][CT];
 #pragma unroll
@@ -242,136 +339,102 @@ __global__ __launch_bounds__(stripe_max_threads(G, CT, D)) void stripe_kernel(St
 #pragma unroll
         for (int c = 0; c < CT; ++c) acc[j][c] = float4v{0.f, 0.f, 0.f, 0.f};
 
-    // ---- staging of chunk ch into buffer `buf`
-    auto stage_async = [&](int ch, char *buf) {
-        const uint32_t lds0 = __builtin_amdgcn_readfirstlane(lds_address(buf));
-        const int k0 = ch * a.kc;
-        const int rows = min(a.kc, a.K - k0);
-        const int ninst = (rows * PIECES + 63) >> 6; // each instruction fills 1 KB of LDS
-        const int r_in = lane / PIECES, pp = lane % PIECES;
-        for (int i = wave; i < ninst; i += waves) {
-            const int r = i * (64 / PIECES) + r_in;
-            if (r < rows) {
-                const int u = (pp >> 1) ^ swz<CT>(r); // logical unit stored at this position
-                const uint16_t *src = a.X + (int64_t)(k0 + r) * a.ldx + col0 + u * 16 + (pp & 1) * 8;
-                load16_to_lds(src, lds0 + (uint32_t)i * 1024u);
-            }
-        }
-    };
-    auto stage_sync = [&](int ch, char *buf) {
-        const int k0 = ch * a.kc;
-        const int rows = min(a.kc, a.K - k0);
-        for (int piece = threadIdx.x; piece < rows * PIECES; piece += nthreads) {
-            const int r = piece / PIECES, pp = piece % PIECES;
-            const int u = (pp >> 1) ^ swz<CT>(r);
-            const int c = col0 + u * 16 + (pp & 1) * 8;
-            const uint16_t *src = a.X + (int64_t)(k0 + r) * a.ldx + c;
-            uint4 v;
-            if (a.vec_ok && c + 8 <= a.N) {
-                v = *reinterpret_cast<const uint4 *>(src);
-            } else {
-                uint32_t e[8];
-#pragma unroll
-                for (int t = 0; t < 8; ++t) e[t] = (c + t < a.N) ? (uint32_t)src[t] : 0u;
-                v = uint4{e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16), e[6] | (e[7] << 16)};
-            }
-            *reinterpret_cast<uint4 *>(buf + r * PITCH + pp * 16) = v;
-        }
-    };
-
-    // ---- this wavefront's step stream (contiguous over all chunks) and its register ring
-    int s = rg >= 0 ? a.rg_ptr[rg] : 0;
-    const int s_all = rg >= 0 ? a.rg_ptr[rg + 1] : 0;
-    uint32_t info[D];
+    uint2 info[D];
     uint4 wf[D][G];
     auto issue = [&](int d, int step) {
         const uint32_t *rec = a.stream + (int64_t)step * REC_DW;
-        info[d] = rec[lane];
-        const uint4 *fr = reinterpret_cast<const uint4 *>(rec + 64) + lane;
+        info[d] = reinterpret_cast<const uint2 *>(rec)[lane];
+        const uint4 *fr = reinterpret_cast<const uint4 *>(rec + 128) + lane;
 #pragma unroll
         for (int j = 0; j < G; ++j) wf[d][j] = fr[j * 64];
     };
-    if (s < s_all) {
-        // same issue order as in the loop (slot by slot), so that the compiler's count of
-        // loads in flight behind each slot is the same on entry and on the back edge
-#pragma unroll
-        for (int d = 0; d < D; ++d) {
-            issue(d, min(s + d, s_all - 1));
-            __builtin_amdgcn_sched_barrier(0);
-        }
-    }
 
-    int ch = -1, since_stage = 0;
-    const char *cur = smem;
-    if constexpr (FAST) stage_async(0, smem);
-    auto advance = [&]() { // make chunk ch+1 the current one
-        ++ch;
-        if constexpr (FAST) {
-            // the staging loads of this chunk were issued before the last `since_stage` record
-            // fetches; vector memory operations complete in order, so once at most D records
-            // (1 + G loads each) are outstanding the staged chunk has landed
-            if (since_stage >= D) wait_vmcnt<D * (1 + G)>();
-            else wait_vmcnt<0>();
-            __syncthreads(); // chunk ch is in LDS for everyone; the other buffer is free
-            if (ch + 1 < a.nch) stage_async(ch + 1, smem + ((ch + 1) & 1) * buf_bytes);
-            since_stage = 0;
-            cur = smem + (ch & 1) * buf_bytes;
-        } else {
-            if (ch) __syncthreads();
-            stage_sync(ch, smem);
-            __syncthreads();
+    int released = 0;   // chunks this wavefront has released
+    int ready_upto = 0; // chunks known to be published
+    bool broken = false;
+    auto wait_published = [&](int chunk) {
+        if (chunk < ready_upto || broken) return;
+        const uint32_t want = (uint32_t)(chunk / R + 1);
+        int spins = 0;
+        while (flag_load(&ready[chunk % R]) < want) {
+            if (++spins > kSpinLimit) {
+                broken = true;
+                if (lane == 0) atomicOr(a.err, 2u);
+                return;
+            }
+            __builtin_amdgcn_s_sleep(1);
+        }
+        ready_upto = chunk + 1;
+    };
+    // Releases go in chunk order, each only after the chunk has been published: the producer's
+    // done counters then never contain a release of a chunk that is not in the ring yet (a
+    // wavefront whose steps skip chunks would otherwise release them ahead of time and let the
+    // producer refill a slot another wavefront still reads).
+    auto release_upto = [&](int upto) {
+        // relaxed + a compiler barrier: the reads of these chunks returned before the MFMAs that
+        // used them were issued, and LDS executes this wavefront's operations in order; a release
+        // would make the compiler drain the prefetch ring at every chunk
+        asm volatile("" ::: "memory");
+        while (released < upto) {
+            wait_published(released);
+            if (lane == 0)
+                __hip_atomic_fetch_add(&done[released % R], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            ++released;
         }
     };
-    advance();
 
-    const int lane_sub = (lane & 3) * 8; // byte offset of this lane's 4 pixels inside a 32-byte unit
     // Every step refills its ring slot unconditionally (past the end of the stream the last
     // record is fetched again and never used): the number of loads in flight behind a slot
     // is then the same on every path, which lets the compiler wait with a partial vmcnt
     // instead of draining the ring.
     if (s < s_all) {
         const int s_last = s_all - 1;
+#pragma unroll
+        for (int d = 0; d < D; ++d) {
+            issue(d, min(s + d, s_last));
+            __builtin_amdgcn_sched_barrier(0); // same issue order as in the loop, slot by slot
+        }
         for (;;) {
 #pragma unroll
             for (int d = 0; d < D; ++d) {
-                const uint32_t inf = info[d];
-                const int r_lo = (int)(inf & 0x3ffu), r_hi = (int)((inf >> 10) & 0x3ffu);
-                const uint32_t flags = __builtin_amdgcn_readfirstlane(inf >> 20);
-                if (flags & 0xfu) {
-                    const int b_lo = r_lo * PITCH + lane_sub, b_hi = r_hi * PITCH + lane_sub;
-                    const int x_lo = swz<CT>(r_lo) << 5, x_hi = swz<CT>(r_hi) << 5;
-                    short8v xf[CT];
+                const uint2 inf = info[d];
+                const uint32_t ctl = __builtin_amdgcn_readfirstlane(inf.y);
+                const int need = (int)(ctl & 0xffffu), rel = (int)(ctl >> 16);
+                // first give back what no later step reads (their reads were consumed by earlier
+                // MFMAs), then wait for the highest chunk this step reads; chunks are published in
+                // order, so that covers every chunk of the step.  Releasing first matters: the
+                // producer may need exactly those slots to bring the awaited chunk in.
+                release_upto(rel);
+                wait_published(need);
+                const uint32_t mask = __builtin_amdgcn_readfirstlane(inf.x >> 28);
+                const int a_lo = (int)((inf.x & 0x3fffu) << 3), a_hi = (int)(((inf.x >> 14) & 0x3fffu) << 3);
+                short8v xf[CT];
 #pragma unroll
-                    for (int c = 0; c < CT; ++c) {
-                        const short4v p0 = lds_read_tr(cur, b_lo + ((c << 5) ^ x_lo));
-                        const short4v p1 = lds_read_tr(cur, b_hi + ((c << 5) ^ x_hi));
-                        xf[c] = __builtin_shufflevector(p0, p1, 0, 1, 2, 3, 4, 5, 6, 7);
-                    }
+                for (int c = 0; c < CT; ++c) {
+                    const short4v p0 = lds_read_tr(smem, a_lo ^ (c << 5));
+                    const short4v p1 = lds_read_tr(smem, a_hi ^ (c << 5));
+                    xf[c] = __builtin_shufflevector(p0, p1, 0, 1, 2, 3, 4, 5, 6, 7);
+                }
 #pragma unroll
-                    for (int j = 0; j < G; ++j) {
-                        if (G == 1 || (flags & (1u << j))) {
-                            const short8v wv = __builtin_bit_cast(short8v, wf[d][j]);
+                for (int j = 0; j < G; ++j) {
+                    if (G == 1 || (mask & (1u << j))) {
+                        const short8v wv = __builtin_bit_cast(short8v, wf[d][j]);
 #pragma unroll
-                            for (int c = 0; c < CT; ++c) acc[j][c] = mfma16<BF16>(xf[c], wv, acc[j][c]);
-                        }
+                        for (int c = 0; c < CT; ++c) acc[j][c] = mfma16<BF16>(xf[c], wv, acc[j][c]);
                     }
                 }
                 issue(d, min(s + D, s_last));
-                ++since_stage;
                 if (s == s_last) goto stream_done;
                 ++s;
-                if ((flags & 0x10u) && ch + 1 < a.nch) advance();
             }
         }
     }
 stream_done:
-    // wavefronts without a row group still take part in every chunk's barriers
-    if (rg < 0)
-        while (ch + 1 < a.nch) advance();
+    // the producer counts a release from every consumer for every chunk
+    release_upto(a.nch);
 
     // ---- store: lane (g = lane/16, n = lane%16) holds pixels col0 + 16*c + 4*g + v of row
     // 16*(G*rg + j) + n.  Rows no block touches are stored as zeros like any other.
-    if (rg < 0) return;
     const int g = lane >> 4, n = lane & 15;
     TY *Yt = static_cast<TY *>(a.Y);
 #pragma unroll
@@ -431,8 +494,7 @@ constexpr int kPrefetchDepth = 4;
 template <bool BF16, typename TY, int G, int CT, bool FAST>
 ubp_status launch_stripe_one(StripeArgs a, int ctile0, int n_coltiles, int waves, hipStream_t st) {
     constexpr int D = kPrefetchDepth;
-    // FAST: two chunk buffers when there is more than one chunk
-    const size_t lds = (size_t)a.kc * (32 * CT) * ((FAST && a.nch > 1) ? 2 : 1);
+    const size_t lds = (size_t)ring_rows(CT) * ring_pitch(CT) + 2 * ring_slots(CT) * sizeof(uint32_t);
     static size_t attr_bytes = 0; // per instantiation; the limit is only ever raised
     if (lds > attr_bytes) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(&stripe_kernel<BF16, TY, G, CT, D, FAST>),
@@ -518,6 +580,10 @@ ubp_status upload(ubp_packed *p) {
         }
         ok = ok && dev_copy(&p->d_values_f32, f.data(), f.size(), &p->device_bytes);
     }
+    {
+        const uint32_t zero = 0;
+        ok = ok && dev_copy(&p->d_error, &zero, 1, &p->device_bytes);
+    }
     if (p->dtype != UBP_F32) {
         for (int s = 0; s < kNumLayouts && ok; ++s) {
             const StripeLayout &L = p->sg[s];
@@ -545,6 +611,7 @@ void release_device(ubp_packed *p) {
     rel(p->d_indptr);
     rel(p->d_indices);
     rel(p->d_values_f32);
+    rel(p->d_error);
     for (int s = 0; s < kNumLayouts; ++s) {
         rel(p->d_sg[s].rg_ptr);
         rel(p->d_sg[s].rg_order);
@@ -607,7 +674,6 @@ ubp_status ubp_spmm_plan(const ubp_packed *p, const void *X_dev, int64_t ldx, in
     int CT = pl.col_tiles ? pl.col_tiles : env_int("UBP_CT", 0);
     int G = pl.sub_stripes ? pl.sub_stripes : env_int("UBP_G", 0);
     int waves = pl.waves ? pl.waves : env_int("UBP_WAVES", 0);
-    int KC = pl.chunk_rows ? pl.chunk_rows : env_int("UBP_KC", 0);
     if (CT == 0) CT = 4;
     if (G == 0) {
         // largest row group that still leaves about two wavefront tiles per SIMD
@@ -615,19 +681,13 @@ ubp_status ubp_spmm_plan(const ubp_packed *p, const void *X_dev, int64_t ldx, in
         G = 4;
         while (G > 1 && ((p->M + 16 * G - 1) / (16 * G)) * coltiles < 2048) G >>= 1;
     }
-    if (CT != 2 && CT != 4 && CT != 8) return UBP_ERR_UNSUPPORTED;
-    if (KC == 0) {
-        // largest chunk whose two buffers fit 128 KB of LDS, not larger than K needs
-        KC = 2048 / CT;
-        while (KC > 256 && KC / 2 >= p->K) KC >>= 1;
-    }
-    const int slot = layout_slot(G, KC);
+    const int slot = layout_slot(G, CT);
     if (slot < 0) return UBP_ERR_UNSUPPORTED;
     const StripeLayout &L = p->sg[slot];
-    if ((size_t)KC * 32 * CT * (L.nch > 1 ? 2 : 1) > 160 * 1024) return UBP_ERR_UNSUPPORTED;
+    if (L.G == 0) return UBP_ERR_UNSUPPORTED; // layouts are not built when K exceeds the records' chunk range
     const int max_waves = stripe_max_waves(G, CT);
-    if (waves == 0) waves = std::min(max_waves, std::max(1, L.nrg));
-    if (waves < 1 || waves > max_waves) return UBP_ERR_UNSUPPORTED;
+    if (waves == 0) waves = std::min(max_waves, L.nrg + 1); // consumers + one producer
+    if (waves < 2 || waves > max_waves) return UBP_ERR_UNSUPPORTED;
 
     StripeArgs a;
     a.rg_ptr = p->d_sg[slot].rg_ptr;
@@ -642,10 +702,10 @@ ubp_status ubp_spmm_plan(const ubp_packed *p, const void *X_dev, int64_t ldx, in
     a.N = N;
     a.nrg = L.nrg;
     a.nch = L.nch;
-    a.kc = L.chunk_rows;
+    a.err = p->d_error;
     a.ctile0 = 0;
     a.n_coltiles = 0;
-    a.n_wgrows = (L.nrg + waves - 1) / waves;
+    a.n_wgrows = (L.nrg + (waves - 1) - 1) / (waves - 1);
     const size_t ysz = (y_dtype == UBP_F32) ? 4 : 2;
     a.vec_ok = (ldx % 8 == 0) && (reinterpret_cast<uintptr_t>(X_dev) % 16 == 0) && ((ldy * ysz) % 16 == 0) &&
                (reinterpret_cast<uintptr_t>(Y_dev) % 16 == 0);
@@ -654,6 +714,17 @@ ubp_status ubp_spmm_plan(const ubp_packed *p, const void *X_dev, int64_t ldx, in
                                   : launch_stripe<true, __bf16>(a, G, CT, waves, st);
     return y_dtype == UBP_F32 ? launch_stripe<false, float>(a, G, CT, waves, st)
                               : launch_stripe<false, _Float16>(a, G, CT, waves, st);
+}
+
+ubp_status ubp_packed_device_error(const ubp_packed *p, uint32_t *flags) {
+    if (!p || !flags || p->device == UBP_HOST_ONLY) return UBP_ERR_INVALID_ARG;
+    ubp::DeviceGuard guard(p->device);
+    if (!guard.ok) return UBP_ERR_DEVICE;
+    if (hipMemcpy(flags, p->d_error, sizeof(uint32_t), hipMemcpyDeviceToHost) != hipSuccess) {
+        (void)hipGetLastError();
+        return UBP_ERR_DEVICE;
+    }
+    return UBP_OK;
 }
 
 ubp_status ubp_spmm(const ubp_packed *p, const void *X_dev, int64_t ldx, int32_t N, void *Y_dev, int64_t ldy,

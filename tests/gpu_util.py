@@ -40,6 +40,7 @@ def run_spmm(W_enc, dtype, bh, bw, blocks, X_enc, y_dtype=None, plan=None, ldx=N
     stream = torch.cuda.current_stream().cuda_stream
     ubp.spmm(packed, Xd.data_ptr(), ldx, N, Yd.data_ptr(), ldy, y_dtype, stream, plan)
     torch.cuda.synchronize()
+    assert packed.device_error() == 0, "a bounded wait inside the kernel ran out"
     out = from_device(Yd, y_dtype)
     if own:
         packed.free()

@@ -43,6 +43,7 @@ SMALL = [  # M, K, N, bh, bw, density: several tiles, ragged tails, odd pitches
     (33, 40, 129, 5, 3, 0.3),
     (48, 520, 72, 2, 6, 0.35),
     (96, 700, 256, 4, 4, 0.25),
+    (40, 2100, 64, 4, 4, 0.02),
     (16, 16, 16, 16, 16, 1.0),
     (257, 31, 40, 1, 1, 0.3),
 ]
@@ -70,12 +71,9 @@ def test_stripe_kernel_small(shape, dtype):
         for y_dtype in (dtype, "f32"):
             Y = run_spmm(W, dtype, bh, bw, blocks, X, y_dtype, _plan(kernel=2, sub_stripes=G, col_tiles=CT))
             check(Y, Yref, Yabs, dtype, y_dtype)
-    for G, CT, KC in [(1, 4, 256), (2, 2, 256), (4, 8, 256), (2, 4, 512), (1, 2, 1024)]:
-        Y = run_spmm(W, dtype, bh, bw, blocks, X, dtype,
-                     _plan(kernel=2, sub_stripes=G, col_tiles=CT, chunk_rows=KC))
+    for G, CT, waves in [(1, 4, 2), (2, 2, 5), (4, 8, 8), (2, 4, 16), (1, 2, 3)]:
+        Y = run_spmm(W, dtype, bh, bw, blocks, X, dtype, _plan(kernel=2, sub_stripes=G, col_tiles=CT, waves=waves))
         check(Y, Yref, Yabs, dtype)
-    Y = run_spmm(W, dtype, bh, bw, blocks, X, dtype, _plan(kernel=2, sub_stripes=1, col_tiles=4, waves=3))
-    check(Y, Yref, Yabs, dtype)
 
 
 @pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
@@ -90,6 +88,23 @@ def test_unaligned_pitches_and_pointers(dtype):
         check(Y, Yref, Yabs, dtype)
         Y = run_spmm(W, dtype, bh, bw, blocks, X, dtype, _plan(kernel=1), ldx=ldx, ldy=ldy)
         check(Y, Yref, Yabs, dtype)
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+def test_uneven_row_groups_share_the_lds_ring(dtype):
+    """K is many times the LDS ring; one row group is dense over all of K, others touch only a
+    few far-apart columns, so wavefronts of one workgroup run through the ring at very different
+    paces (a slot must not be refilled while the slow one still needs it)."""
+    M, K, N, bh, bw = 112, 3000, 200, 8, 8
+    blocks = [(0, c) for c in range(0, K - bw, 12)] + [(9, c) for c in range(3, K - bw, 40)]
+    blocks += [(40, 0), (40, 2900), (70, 1500), (100, 7), (100, 1000), (100, 2990)]
+    W = make_weights(M, K, 31, dtype)
+    X = make_activations(K, N, 32, dtype, "normal")
+    Yref, Yabs = _oracle(W, dtype, bh, bw, blocks, X)
+    for G, CT in itertools.product((1, 2, 4), (2, 4, 8)):
+        for rep in range(2):
+            Y = run_spmm(W, dtype, bh, bw, blocks, X, "f32", _plan(kernel=2, sub_stripes=G, col_tiles=CT))
+            check(Y, Yref, Yabs, dtype, "f32")
 
 
 # ------------------------------------------------------------------ exact special cases
@@ -207,3 +222,6 @@ def test_layer_full_size_sampled_rows(name):
     Yv = run_spmm(W, cfg.dtype, cfg.bh, cfg.bw, blocks, X, "f32", _plan(kernel=1))
     check(Yv[rows], Yref, Yabs, cfg.dtype, "f32")
     assert np.abs(Yv - Y32).max() <= 1e-4 * np.abs(Yref).max()
+    for G, CT in [(1, 8), (2, 8), (4, 4), (2, 2)]:
+        Yp = run_spmm(W, cfg.dtype, cfg.bh, cfg.bw, blocks, X, "f32", _plan(kernel=2, sub_stripes=G, col_tiles=CT))
+        assert np.abs(Yv - Yp).max() <= 1e-4 * np.abs(Yref).max(), (G, CT)
