@@ -358,8 +358,9 @@ static void build_one(ubp_packed *p, StripeLayout &L, int G, int CT) {
             }
         }
         for (const Entry &e : entries) colslot[(size_t)e.k] = -1;
-        std::sort(entries.begin(), entries.end(), [](const Entry &a, const Entry &b) {
-            const int wa = a.k / kWindow, wb = b.k / kWindow;
+        const int window = ring_window(CT);
+        std::sort(entries.begin(), entries.end(), [window](const Entry &a, const Entry &b) {
+            const int wa = a.k / window, wb = b.k / window;
             if (wa != wb) return wa < wb;
             if (a.mask != b.mask) return a.mask < b.mask;
             return a.k < b.k;
@@ -373,7 +374,7 @@ static void build_one(ubp_packed *p, StripeLayout &L, int G, int CT) {
             while (n < (size_t)kStep && pos + n < entries.size()) {
                 const int c = entries[pos + n].k / kSlotRows;
                 const int lo = std::min(cmin, c), hi = std::max(cmax, c);
-                if (hi - lo > R - 2) break;
+                if (hi - lo > R / 2) break; // at most half the ring, whatever the window size
                 cmin = lo;
                 cmax = hi;
                 ++n;
@@ -386,7 +387,7 @@ static void build_one(ubp_packed *p, StripeLayout &L, int G, int CT) {
             steps[s].rel = (int)m; // chunks below this are never read by this or any later step
             // a consumer holds chunks rel..cmax at this step; they must fit the ring with a slot
             // to spare or producer and consumer could wait for each other
-            if (steps[s].cmax - steps[s].rel > R - 2) {
+            if (steps[s].cmax - steps[s].rel > R / 2 + 1) {
                 L.G = 0; // unusable; the launcher reports UBP_ERR_UNSUPPORTED
                 return;
             }
@@ -431,12 +432,27 @@ static void build_one(ubp_packed *p, StripeLayout &L, int G, int CT) {
             }
             ++L.nsteps;
         }
+        // empty steps up to a multiple of the prefetch depth: they read nothing, wait for
+        // nothing and hand back every chunk
+        while ((L.nsteps - L.rg_ptr[(size_t)rg]) % kPrefetchDepth != 0) {
+            const size_t rec = L.stream.size();
+            L.stream.resize(rec + rec_dw, 0u);
+            for (int lane = 0; lane < 64; ++lane) L.stream[rec + 2 * lane + 1] = (uint32_t)L.nch << 16;
+            ++L.nsteps;
+        }
     }
     L.rg_ptr[(size_t)L.nrg] = (int32_t)L.nsteps;
+    // spare records: the kernel fetches kPrefetchDepth steps ahead without checking for the end
+    L.stream.resize(L.stream.size() + rec_dw * kPrefetchDepth, 0u);
     L.rg_order.resize((size_t)L.nrg);
     std::iota(L.rg_order.begin(), L.rg_order.end(), 0);
     std::stable_sort(L.rg_order.begin(), L.rg_order.end(),
                      [&](int32_t a, int32_t b) { return rg_weight[(size_t)a] > rg_weight[(size_t)b]; });
+    L.sorted_steps.resize((size_t)L.nrg);
+    for (int i = 0; i < L.nrg; ++i) {
+        const int32_t rg = L.rg_order[(size_t)i];
+        L.sorted_steps[(size_t)i] = L.rg_ptr[(size_t)rg + 1] - L.rg_ptr[(size_t)rg];
+    }
 }
 
 void build_stripe_layouts(ubp_packed *p) {

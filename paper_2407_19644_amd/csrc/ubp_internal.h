@@ -11,7 +11,7 @@ namespace ubp {
 constexpr int kStripe = 16;    // rows of one MFMA output tile (aligned row stripe)
 constexpr int kStep = 32;      // gathered X rows consumed by one 16x16x32 MFMA
 constexpr int kSlotRows = 64;  // X rows per slot of the LDS ring (the unit the producer stages)
-constexpr int kWindow = 128;   // entries are grouped by stripe set inside windows of this many X rows
+constexpr int kPrefetchDepth = 4; // step records a wavefront keeps in flight; row groups hold a multiple of it
 constexpr int kNumG = 3;       // stripes per wavefront: 1, 2, 4
 constexpr int kNumCT = 3;      // 16-column tiles per wavefront: 2, 4, 8
 constexpr int kNumLayouts = kNumG * kNumCT;
@@ -26,11 +26,15 @@ inline int layout_slot(int G, int CT) {
 inline int slot_G(int slot) { return 1 << (slot / kNumCT); }
 inline int slot_CT(int slot) { return 2 << (slot % kNumCT); }
 
-// LDS ring geometry for a column-tile width: rows of 32*CT bytes, 64 KB (CT = 2, 4) or
-// 128 KB (CT = 8), always a power-of-two number of rows so that ring row = X row mod rows.
+// LDS ring geometry for a column-tile width: rows of 32*CT bytes, 128 KB in all, always a
+// power-of-two number of rows so that ring row = X row mod rows.
 constexpr int ring_pitch(int CT) { return 32 * CT; }
-constexpr int ring_rows(int CT) { return CT == 2 ? 1024 : 512; }
+constexpr int ring_rows(int CT) { return 131072 / ring_pitch(CT); }
 constexpr int ring_slots(int CT) { return ring_rows(CT) / kSlotRows; }
+// Entries are grouped by stripe set inside windows of this many X rows (a quarter of the ring:
+// a step may straddle two windows, and the rest of the ring is left to the drift between
+// wavefronts and to the chunks the producer has in flight).
+constexpr int ring_window(int CT) { return ring_rows(CT) / 4; }
 
 // Position of the 32-byte unit u (16 pixels) inside ring row r is u ^ ring_swizzle(r): LDS
 // has 64 four-byte banks, and this spreads 16 consecutive rows of one unit over all of them.
@@ -41,15 +45,16 @@ constexpr int ring_swizzle(int CT, int r) { return CT == 2 ? ((r >> 2) & 1) : CT
 // Rows are cut into row groups of 16*G aligned rows.  For a row group the columns of W
 // that hold at least one kept weight in it are its "entries"; an entry is one row of X
 // to gather plus the 16*G weights of that column (zero where no block covers the row).
-// Entries are ordered by window of kWindow X rows, inside a window by the set of stripes
+// Entries are ordered by window of ring_window(CT) X rows, inside a window by the set of stripes
 // they touch and then by column, and grouped 32 at a time into "steps" whose rows fit the
 // LDS ring together.
 struct StripeLayout {
     int G = 0, CT = 0;
     int nrg = 0;     // row groups
     int nch = 0;     // slots (chunks of kSlotRows X rows) the producer stages: ceil(K / 64)
-    std::vector<int32_t> rg_ptr;     // [nrg + 1] first step of each row group
+    std::vector<int32_t> rg_ptr;     // [nrg + 1] first step of each row group (step counts are multiples of kPrefetchDepth)
     std::vector<int32_t> rg_order;   // row groups, heaviest (most MFMAs) first
+    std::vector<int32_t> sorted_steps; // [nrg] step count of rg_order[i] (host only: work estimates)
     // One fixed-size record per step, (128 + 256*G) dwords, so that the address of any later
     // step is known without reading metadata:
     //   dwords 0..127 : per lane a pair {addr, ctl}
@@ -61,6 +66,8 @@ struct StripeLayout {
     //                                of leading chunks that no step from here on reads
     //   then G x 256 dwords: weight fragment of stripe j in MFMA operand order (lane-major,
     //                        8 16-bit values per lane), all zero when the step has no weight there
+    // A row group's last steps may be empty (no stripes, nothing read): they pad its step count
+    // to a multiple of kPrefetchDepth so that the kernel's unrolled loop has a single exit.
     std::vector<uint32_t> stream;
     int64_t nsteps = 0;
     int64_t total_mfma = 0; // MFMA issues per 16-column tile (steps x stripes with weights)

@@ -14,8 +14,10 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <cmath>
 #include <cstdlib>
 #include <cstring>
+#include <vector>
 
 #include "ubp_internal.h"
 
@@ -146,6 +148,7 @@ struct StripeArgs {
     int64_t ldx, ldy;
     int M, K, N;
     int nrg, nch;            // row groups, 64-row chunks of X
+    int ring_bytes;          // bytes of the LDS ring actually used (all of K when K is shorter than the ring)
     int ctile0, n_coltiles;  // first column tile of this launch, number of tiles in it
     int n_wgrows;
     int vec_ok;              // X and Y allow 16-byte vector access on every row
@@ -170,8 +173,9 @@ __device__ __forceinline__ short4v lds_read_tr(const char *lds_base, int byte_of
 // the load as a pending LDS write, which would make it wait for ALL outstanding vector
 // memory operations before every LDS read.  Ordering against the LDS reads of the staged
 // data is done by hand (wait_vmcnt, then the slot's ready flag).
-__device__ __forceinline__ void load16_to_lds(const void *gsrc, uint32_t lds_base) {
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gsrc), "s"(lds_base));
+__device__ __forceinline__ void load16_to_lds(const void *gbase, uint32_t lane_off, uint32_t lds_base) {
+    // address = gbase (wave-uniform, in SGPRs) + lane_off (32-bit per-lane byte offset)
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(lane_off), "s"(gbase), "s"(lds_base));
 }
 
 __device__ __forceinline__ uint32_t lds_address(const char *p) {
@@ -223,14 +227,16 @@ __global__ __launch_bounds__(stripe_max_threads(G, CT, D)) void stripe_kernel(St
     constexpr int RR = ring_rows(CT), R = ring_slots(CT), KS = kSlotRows;
     constexpr int REC_DW = 128 + 256 * G;
     constexpr int NINST = KS * PIECES / 64; // direct-to-LDS instructions per chunk (1 KB each)
-    constexpr int LAG = 32 / NINST;         // chunks kept in flight before their readiness is published
+    constexpr int LAG = 56 / NINST;         // chunks kept in flight before their readiness is published
     extern __shared__ __attribute__((aligned(1024))) char smem[];
-    uint32_t *ready = reinterpret_cast<uint32_t *>(smem + RR * PITCH); // [R] generation + 1 of the chunk in the slot
+    uint32_t *ready = reinterpret_cast<uint32_t *>(smem + a.ring_bytes); // [R] generation + 1 of the chunk in the slot
     uint32_t *done = ready + R;                                        // [R] releases received, all generations
 
     // workgroup -> (column tile, workgroup row); consecutive workgroup ids go round-robin
     // over the 8 XCDs, so tiles are dealt by id mod 8 and all row groups of one column tile
-    // run on one XCD (they share the X tile in that XCD's L2).
+    // run on one XCD at about the same time: they share the X tile in that XCD's L2, which
+    // measured better than the alternative of keeping one workgroup row's step records in L2
+    // and streaming X once per workgroup row.
     const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
     const int my_tiles = (a.n_coltiles - xcd + 7) >> 3;
     if (local >= my_tiles * a.n_wgrows) return;
@@ -262,8 +268,24 @@ __global__ __launch_bounds__(stripe_max_threads(G, CT, D)) void stripe_kernel(St
                 ++published;
             }
         };
+        __builtin_amdgcn_s_setprio(3); // little work, but everyone else waits for it
         const uint32_t ring0 = __builtin_amdgcn_readfirstlane(lds_address(smem));
         const int r_in = lane / PIECES, pp = lane % PIECES;
+        // FAST: byte offset of this lane's 16-byte piece from the chunk's first element, for each
+        // of the NINST instructions of a chunk.  The swizzle repeats every 8 rows at most, chunks
+        // are 64 rows, so the offsets are the same for every chunk; only the base moves.
+        uint32_t voff[NINST];
+        auto piece_offset = [&](int i, int rows) {
+            const int r = i * (64 / PIECES) + r_in;              // row inside the chunk
+            const int u = (pp >> 1) ^ ring_swizzle(CT, r);       // logical unit stored at this position
+            // rows past K load the chunk's last row again (never read): every chunk then issues
+            // exactly NINST loads, which the in-order vmcnt bookkeeping relies on
+            return (uint32_t)(((int64_t)min(r, rows - 1) * a.ldx + u * 16 + (pp & 1) * 8) * 2);
+        };
+        if constexpr (FAST) {
+#pragma unroll
+            for (int i = 0; i < NINST; ++i) voff[i] = piece_offset(i, KS);
+        }
         for (int c = 0; c < a.nch; ++c) {
             const int slot = c % R;
             if (c >= R && !broken) {
@@ -288,14 +310,13 @@ __global__ __launch_bounds__(stripe_max_threads(G, CT, D)) void stripe_kernel(St
             const int rows = min(KS, a.K - k0);
             if constexpr (FAST) {
                 const uint32_t lds0 = ring0 + (uint32_t)(slot * KS * PITCH);
+                const uint16_t *base = a.X + (int64_t)k0 * a.ldx + col0; // wave-uniform
+                if (rows == KS) {
 #pragma unroll
-                for (int i = 0; i < NINST; ++i) {
-                    const int r = i * (64 / PIECES) + r_in;             // row inside the slot
-                    const int u = (pp >> 1) ^ ring_swizzle(CT, slot * KS + r); // logical unit stored at this position
-                    // rows past K load the chunk's last row again (never read): every chunk then
-                    // issues exactly NINST loads, which the in-order vmcnt bookkeeping relies on
-                    const uint16_t *src = a.X + (int64_t)(k0 + min(r, rows - 1)) * a.ldx + col0 + u * 16 + (pp & 1) * 8;
-                    load16_to_lds(src, lds0 + (uint32_t)i * 1024u);
+                    for (int i = 0; i < NINST; ++i) load16_to_lds(base, voff[i], lds0 + (uint32_t)i * 1024u);
+                } else {
+#pragma unroll
+                    for (int i = 0; i < NINST; ++i) load16_to_lds(base, piece_offset(i, rows), lds0 + (uint32_t)i * 1024u);
                 }
                 if (c + 1 - published > LAG) {
                     wait_vmcnt<LAG * NINST>(); // vector memory completes in order: chunks <= c - LAG have landed
@@ -329,9 +350,9 @@ __global__ __launch_bounds__(stripe_max_threads(G, CT, D)) void stripe_kernel(St
     if (wave >= active) return; // no row group left for this wavefront
 
     // ------------------------------------------------------------------ consumer
-    const int rg = a.rg_order[rg0 + wave];
-    int s = a.rg_ptr[rg];
-    const int s_all = a.rg_ptr[rg + 1];
+    const int rg = __builtin_amdgcn_readfirstlane(a.rg_order[rg0 + wave]);
+    int s = __builtin_amdgcn_readfirstlane(a.rg_ptr[rg]);
+    const int s_all = __builtin_amdgcn_readfirstlane(a.rg_ptr[rg + 1]);
 
     float4v acc[G][CT];
 #pragma unroll
@@ -339,14 +360,19 @@ __global__ __launch_bounds__(stripe_max_threads(G, CT, D)) void stripe_kernel(St
 #pragma unroll
         for (int c = 0; c < CT; ++c) acc[j][c] = float4v{0.f, 0.f, 0.f, 0.f};
 
+    // Record of step t: wave-uniform base (kept in SGPRs, advanced by one record per step) plus
+    // a fixed per-lane offset, so that a refill costs no vector ALU work.  The stream carries D
+    // spare records at its end: refills run D steps ahead and simply read on past the row
+    // group's last step (those records are never used).
     uint2 info[D];
     uint4 wf[D][G];
-    auto issue = [&](int d, int step) {
-        const uint32_t *rec = a.stream + (int64_t)step * REC_DW;
-        info[d] = reinterpret_cast<const uint2 *>(rec)[lane];
-        const uint4 *fr = reinterpret_cast<const uint4 *>(rec + 128) + lane;
+    const char *rec_next = reinterpret_cast<const char *>(a.stream) + (int64_t)s * (REC_DW * 4);
+    const uint32_t lane8 = (uint32_t)lane * 8u, lane16 = (uint32_t)lane * 16u;
+    auto issue = [&](int d) {
+        info[d] = *reinterpret_cast<const uint2 *>(rec_next + lane8);
 #pragma unroll
-        for (int j = 0; j < G; ++j) wf[d][j] = fr[j * 64];
+        for (int j = 0; j < G; ++j) wf[d][j] = *reinterpret_cast<const uint4 *>(rec_next + 512 + j * 1024 + lane16);
+        rec_next += REC_DW * 4;
     };
 
     int released = 0;   // chunks this wavefront has released
@@ -358,8 +384,7 @@ __global__ __launch_bounds__(stripe_max_threads(G, CT, D)) void stripe_kernel(St
         int spins = 0;
         while (flag_load(&ready[chunk % R]) < want) {
             if (++spins > kSpinLimit) {
-                broken = true;
-                if (lane == 0) atomicOr(a.err, 2u);
+                broken = true; // reported after the stream loop (no global atomic inside it)
                 return;
             }
             __builtin_amdgcn_s_sleep(1);
@@ -383,18 +408,18 @@ __global__ __launch_bounds__(stripe_max_threads(G, CT, D)) void stripe_kernel(St
         }
     };
 
-    // Every step refills its ring slot unconditionally (past the end of the stream the last
-    // record is fetched again and never used): the number of loads in flight behind a slot
-    // is then the same on every path, which lets the compiler wait with a partial vmcnt
-    // instead of draining the ring.
+    // The loop body is D steps with no exit in between (row groups hold a multiple of D steps,
+    // the last ones possibly empty), and every step refills its ring slot unconditionally.  The number of
+    // loads in flight behind a slot is then the same on every path into every step, which
+    // lets the compiler wait with a partial vmcnt instead of draining the ring.
+    static_assert(D == kPrefetchDepth, "row groups are padded to a multiple of the prefetch depth");
     if (s < s_all) {
-        const int s_last = s_all - 1;
 #pragma unroll
         for (int d = 0; d < D; ++d) {
-            issue(d, min(s + d, s_last));
+            issue(d);
             __builtin_amdgcn_sched_barrier(0); // same issue order as in the loop, slot by slot
         }
-        for (;;) {
+        for (; s < s_all; s += D) {
 #pragma unroll
             for (int d = 0; d < D; ++d) {
                 const uint2 inf = info[d];
@@ -407,29 +432,29 @@ __global__ __launch_bounds__(stripe_max_threads(G, CT, D)) void stripe_kernel(St
                 release_upto(rel);
                 wait_published(need);
                 const uint32_t mask = __builtin_amdgcn_readfirstlane(inf.x >> 28);
-                const int a_lo = (int)((inf.x & 0x3fffu) << 3), a_hi = (int)(((inf.x >> 14) & 0x3fffu) << 3);
-                short8v xf[CT];
+                if (mask) {
+                    const int a_lo = (int)((inf.x & 0x3fffu) << 3), a_hi = (int)(((inf.x >> 14) & 0x3fffu) << 3);
+                    short8v xf[CT];
 #pragma unroll
-                for (int c = 0; c < CT; ++c) {
-                    const short4v p0 = lds_read_tr(smem, a_lo ^ (c << 5));
-                    const short4v p1 = lds_read_tr(smem, a_hi ^ (c << 5));
-                    xf[c] = __builtin_shufflevector(p0, p1, 0, 1, 2, 3, 4, 5, 6, 7);
-                }
+                    for (int c = 0; c < CT; ++c) {
+                        const short4v p0 = lds_read_tr(smem, a_lo ^ (c << 5));
+                        const short4v p1 = lds_read_tr(smem, a_hi ^ (c << 5));
+                        xf[c] = __builtin_shufflevector(p0, p1, 0, 1, 2, 3, 4, 5, 6, 7);
+                    }
 #pragma unroll
-                for (int j = 0; j < G; ++j) {
-                    if (G == 1 || (mask & (1u << j))) {
-                        const short8v wv = __builtin_bit_cast(short8v, wf[d][j]);
+                    for (int j = 0; j < G; ++j) {
+                        if (mask & (1u << j)) {
+                            const short8v wv = __builtin_bit_cast(short8v, wf[d][j]);
 #pragma unroll
-                        for (int c = 0; c < CT; ++c) acc[j][c] = mfma16<BF16>(xf[c], wv, acc[j][c]);
+                            for (int c = 0; c < CT; ++c) acc[j][c] = mfma16<BF16>(xf[c], wv, acc[j][c]);
+                        }
                     }
                 }
-                issue(d, min(s + D, s_last));
-                if (s == s_last) goto stream_done;
-                ++s;
+                issue(d);
             }
         }
     }
-stream_done:
+    if (broken && lane == 0) atomicOr(a.err, 2u);
     // the producer counts a release from every consumer for every chunk
     release_upto(a.nch);
 
@@ -489,12 +514,10 @@ ubp_status launch_wros(const ubp_packed *p, const void *X, int64_t ldx, int N, v
                : launch_wros_bh<TX, TY, 1>(p, X, ldx, N, Y, ldy, rpr, st);
 }
 
-constexpr int kPrefetchDepth = 4;
-
 template <bool BF16, typename TY, int G, int CT, bool FAST>
 ubp_status launch_stripe_one(StripeArgs a, int ctile0, int n_coltiles, int waves, hipStream_t st) {
     constexpr int D = kPrefetchDepth;
-    const size_t lds = (size_t)ring_rows(CT) * ring_pitch(CT) + 2 * ring_slots(CT) * sizeof(uint32_t);
+    const size_t lds = (size_t)a.ring_bytes + 2 * ring_slots(CT) * sizeof(uint32_t);
     static size_t attr_bytes = 0; // per instantiation; the limit is only ever raised
     if (lds > attr_bytes) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(&stripe_kernel<BF16, TY, G, CT, D, FAST>),
@@ -517,10 +540,12 @@ ubp_status launch_stripe_inst(const StripeArgs &a, int waves, hipStream_t st) {
     // full column tiles with aligned rows take the asynchronous staging path; a ragged last
     // tile (or everything, when rows are not 16-byte aligned) takes the synchronous one
     const int total = (a.N + 16 * CT - 1) / (16 * CT);
-    const int full = a.vec_ok ? a.N / (16 * CT) : 0;
+    // (the producer addresses a chunk with 32-bit lane offsets: 64 rows of ldx elements must fit)
+    const int full = (a.vec_ok && a.ldx <= (int64_t(1) << 24)) ? a.N / (16 * CT) : 0;
     ubp_status rc = UBP_OK;
     if (full > 0) rc = launch_stripe_one<BF16, TY, G, CT, true>(a, 0, full, waves, st);
-    if (rc == UBP_OK && total > full) rc = launch_stripe_one<BF16, TY, G, CT, false>(a, full, total - full, waves, st);
+    if (rc == UBP_OK && total > full)
+        rc = launch_stripe_one<BF16, TY, G, CT, false>(a, full, total - full, waves, st);
     return rc;
 }
 
@@ -674,19 +699,52 @@ ubp_status ubp_spmm_plan(const ubp_packed *p, const void *X_dev, int64_t ldx, in
     int CT = pl.col_tiles ? pl.col_tiles : env_int("UBP_CT", 0);
     int G = pl.sub_stripes ? pl.sub_stripes : env_int("UBP_G", 0);
     int waves = pl.waves ? pl.waves : env_int("UBP_WAVES", 0);
-    if (CT == 0) CT = 4;
-    if (G == 0) {
-        // largest row group that still leaves about two wavefront tiles per SIMD
-        const int64_t coltiles = (N + 16 * CT - 1) / (16 * CT);
-        G = 4;
-        while (G > 1 && ((p->M + 16 * G - 1) / (16 * G)) * coltiles < 2048) G >>= 1;
+    if ((G != 0 && G != 1 && G != 2 && G != 4) || (CT != 0 && CT != 2 && CT != 4 && CT != 8)) return UBP_ERR_UNSUPPORTED;
+    {
+        // Pick the tile shape with the smallest estimated time.  What a workgroup pulls into its
+        // CU (its row groups' step records plus the X tile, once per workgroup) is what bounds
+        // the large layers; small layers are bounded by how many rounds of workgroups the chip
+        // needs and by a workgroup's start-up and store latency.
+        double best = 0.0;
+        int bestG = 0, bestCT = 0;
+        for (int g = 1; g <= 4; g *= 2)
+            for (int ct = 2; ct <= 8; ct *= 2) {
+                if ((G && g != G) || (CT && ct != CT)) continue;
+                const StripeLayout &Lc = p->sg[layout_slot(g, ct)];
+                if (Lc.G == 0) continue;
+                const int mw = waves ? waves : stripe_max_waves(g, ct);
+                if (mw < 2 || mw > stripe_max_waves(g, ct)) continue;
+                const int rows_wg = (Lc.nrg + (mw - 1) - 1) / (mw - 1);           // workgroup rows
+                const int nc = (Lc.nrg + rows_wg - 1) / rows_wg;                   // consumers per workgroup
+                const int64_t ncol = (N + 16 * ct - 1) / (16 * ct);
+                const double rec = (128 + 256 * g) * 4.0;
+                const double bytes = (double)ncol * ((double)Lc.nsteps * rec + (double)rows_wg * p->K * 32.0 * ct);
+                const int ring = std::min(ring_rows(ct), Lc.nch * kSlotRows) * ring_pitch(ct);
+                const int wave_slots = stripe_max_threads(g, ct, kPrefetchDepth) == 1024 ? 16 : 8;
+                const int resident = std::max(1, std::min((160 * 1024) / (ring + 256), wave_slots / (nc + 1)));
+                const double rounds = std::ceil((double)(ncol * rows_wg) / (256.0 * resident));
+                const double heaviest = Lc.sorted_steps.empty() ? 0.0 : (double)Lc.sorted_steps[0];
+                const double busy = std::min(1.0, (double)(ncol * rows_wg) / 256.0); // CUs that get a workgroup
+                double t = std::max(bytes / (9.0e6 * busy), rounds * (5.0 + 0.3 * heaviest)); // microseconds
+                if (N % (16 * ct) != 0) t += 10.0; // the ragged last column tile takes the slow staging path
+                if (bestG == 0 || t < best) {
+                    best = t;
+                    bestG = g;
+                    bestCT = ct;
+                }
+            }
+        if (bestG == 0) return UBP_ERR_UNSUPPORTED;
+        G = bestG;
+        CT = bestCT;
     }
     const int slot = layout_slot(G, CT);
-    if (slot < 0) return UBP_ERR_UNSUPPORTED;
     const StripeLayout &L = p->sg[slot];
-    if (L.G == 0) return UBP_ERR_UNSUPPORTED; // layouts are not built when K exceeds the records' chunk range
     const int max_waves = stripe_max_waves(G, CT);
-    if (waves == 0) waves = std::min(max_waves, L.nrg + 1); // consumers + one producer
+    if (waves == 0) {
+        // as few workgroup rows as the wavefront limit allows, consumers spread evenly over them
+        const int rows_wg = (L.nrg + (max_waves - 1) - 1) / (max_waves - 1);
+        waves = (L.nrg + rows_wg - 1) / rows_wg + 1; // consumers + one producer
+    }
     if (waves < 2 || waves > max_waves) return UBP_ERR_UNSUPPORTED;
 
     StripeArgs a;
@@ -702,6 +760,7 @@ ubp_status ubp_spmm_plan(const ubp_packed *p, const void *X_dev, int64_t ldx, in
     a.N = N;
     a.nrg = L.nrg;
     a.nch = L.nch;
+    a.ring_bytes = std::min(ring_rows(CT), L.nch * kSlotRows) * ring_pitch(CT);
     a.err = p->d_error;
     a.ctile0 = 0;
     a.n_coltiles = 0;
