@@ -166,6 +166,9 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--no-graph", action="store_true", help="launch step by step instead of replaying a HIP graph")
     ap.add_argument("--hot", action="store_true", help="reuse one buffer set (cache-resident timing)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain elementwise kernel over 256 MiB 3 times (reads 256 MiB, writes 256 MiB: "
+                         "known traffic, to scale rocprofv3 byte counters)")
     ap.add_argument("--kernel", type=int, default=0)
     ap.add_argument("--G", type=int, default=0)
     ap.add_argument("--CT", type=int, default=0)
@@ -184,6 +187,13 @@ def main():
     plan_kw = {k: v for k, v in (("kernel", args.kernel), ("sub_stripes", args.G), ("col_tiles", args.CT),
                                  ("waves", args.waves)) if v}
     use_graph = not args.no_graph
+    if args.copy_calibration:
+        src = torch.empty(128 << 20, dtype=torch.bfloat16, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.add(src, 1.0, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
     head, data = measure(args.config, args.steps, args.warmup, args.y_dtype, plan_kw, use_graph, args.hot)
     per = {}
     if not args.only:
