@@ -129,11 +129,20 @@ ubp_status ubp_spmm(const ubp_packed *p, const void *X_dev, int64_t ldx, int32_t
  *                dtype, bh <= 16); 2 = MFMA kernel on aligned 16-row stripes (f16 / bf16).
  *   sub_stripes: MFMA kernel, 16-row stripes per wavefront (1, 2 or 4).
  *   col_tiles  : MFMA kernel, 16-column tiles per wavefront (2, 4 or 8).
- *   waves      : wavefronts per workgroup (MFMA kernel: 2..16, one of them stages X).
+ *   waves      : wavefronts per workgroup (MFMA kernel: producers + 1 .. 16).
  *   rows_per_range : WROS kernel, output rows owned by one workgroup row (multiple of bh).
+ *   producers  : MFMA kernel, wavefronts of a workgroup that stage X into LDS (1, 2 or 4);
+ *                the others each own a row group.
+ *   wg_rows    : MFMA kernel, workgroups that share one column tile (each takes a share of
+ *                the row groups).  Free only when the staged tile holds all K rows of X at
+ *                once (K <= 4096 / col_tiles); otherwise it must be 0 or
+ *                ceil(row groups / (waves - producers)).
+ *   native     : MFMA kernel, private weight layout: 1 = columns of all blocks of a row group
+ *                merged, one operand per stripe; 2 = block-native, whole blocks and one operand
+ *                shared by the stripes (needs bh <= 16, bw in {4, 8, 16, 32}, sub_stripes > 1).
  */
 typedef struct {
-    int32_t kernel, sub_stripes, col_tiles, waves, rows_per_range, reserved[3];
+    int32_t kernel, sub_stripes, col_tiles, waves, rows_per_range, producers, wg_rows, native;
 } ubp_plan;
 
 ubp_status ubp_spmm_plan(const ubp_packed *p, const void *X_dev, int64_t ldx, int32_t N,
@@ -155,6 +164,22 @@ ubp_status ubp_packed_device_error(const ubp_packed *p, uint32_t *flags);
  * 8 bytes of all device-side copies.  Unknown `what` returns -1.
  */
 int64_t ubp_packed_info(const ubp_packed *p, int32_t what);
+
+/*
+ * Read-only view of one of the MFMA kernel's private weight layouts (host copies; valid
+ * until ubp_packed_free), so that the host-side re-layout can be checked without a GPU:
+ * decoding the step records must give back the dense matrix.  sub_stripes / col_tiles /
+ * native name the layout as in ubp_plan (native: 1 merged columns, 2 block-native).
+ *   rg_ptr   : int32[row groups + 1], first step record of each row group
+ *   rg_order : int32[row groups], row groups by decreasing work
+ *   stream   : uint32[stream_words], the step records (format: comment of StripeLayout in
+ *              csrc/ubp_internal.h)
+ * Returns UBP_ERR_UNSUPPORTED when that layout was not built for this matrix (fp32, K too
+ * large, block shape not eligible).  Any output pointer may be NULL.
+ */
+ubp_status ubp_packed_layout(const ubp_packed *p, int32_t sub_stripes, int32_t col_tiles, int32_t native,
+                             int32_t *row_groups, const int32_t **rg_ptr, const int32_t **rg_order,
+                             const uint32_t **stream, int64_t *stream_words);
 
 /* Releases host and device memory of the handle (NULL is allowed).  Must not be called
  * while a ubp_spmm using the handle is still running on the device. */

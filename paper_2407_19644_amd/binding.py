@@ -13,11 +13,17 @@ _LIB_PATH = os.path.join(_HERE, "libubp.so")
 
 UBP_OK = 0
 UBP_HOST_ONLY = -1
+HOST_ONLY = UBP_HOST_ONLY
+
+
+def layout_slot(sub_stripes, col_tiles):
+    """Index of a (stripes per wavefront, column tiles per wavefront) layout in ubp_packed_info's 100+ / 200+ ... ranges."""
+    return {1: 0, 2: 1, 4: 2}[sub_stripes] * 3 + {2: 0, 4: 1, 8: 2}[col_tiles]
 DTYPES = {"f32": 0, "f16": 1, "bf16": 2}
 _NP_OF = {"f32": np.float32, "f16": np.float16, "bf16": np.uint16}
 EXPORTS = ("ubp_target_block_count", "ubp_select_reference", "ubp_pack", "ubp_packed_indptr",
            "ubp_packed_indices", "ubp_packed_values", "ubp_spmm", "ubp_spmm_plan", "ubp_packed_info",
-           "ubp_packed_free", "ubp_status_string", "ubp_packed_device_error")
+           "ubp_packed_free", "ubp_status_string", "ubp_packed_device_error", "ubp_packed_layout")
 
 
 class UBPError(RuntimeError):
@@ -29,7 +35,8 @@ class UBPError(RuntimeError):
 class Plan(ctypes.Structure):
     """Mirror of ubp_plan; zero fields mean 'choose automatically'."""
     _fields_ = [("kernel", ctypes.c_int32), ("sub_stripes", ctypes.c_int32), ("col_tiles", ctypes.c_int32),
-                ("waves", ctypes.c_int32), ("rows_per_range", ctypes.c_int32), ("reserved", ctypes.c_int32 * 3)]
+                ("waves", ctypes.c_int32), ("rows_per_range", ctypes.c_int32), ("producers", ctypes.c_int32),
+                ("wg_rows", ctypes.c_int32), ("native", ctypes.c_int32)]
 
 
 _lib = None
@@ -66,6 +73,9 @@ def load_library():
     L.ubp_packed_info.restype = i64
     L.ubp_packed_device_error.argtypes = [vp, ctypes.POINTER(ctypes.c_uint32)]
     L.ubp_packed_device_error.restype = ctypes.c_int
+    L.ubp_packed_layout.argtypes = [vp, i32, i32, i32, ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(vp),
+                                    ctypes.POINTER(vp), ctypes.POINTER(vp), pi64]
+    L.ubp_packed_layout.restype = ctypes.c_int
     L.ubp_packed_free.argtypes = [vp]
     L.ubp_packed_free.restype = None
     L.ubp_status_string.argtypes = [ctypes.c_int]
@@ -112,6 +122,23 @@ class Packed:
 
     def info(self, what):
         return int(load_library().ubp_packed_info(self.handle, what))
+
+    def layout(self, sub_stripes, col_tiles, native=1):
+        """ubp_packed_layout -> (rg_ptr int32[nrg + 1], rg_order int32[nrg], stream uint32[...]) as copies."""
+        nrg = ctypes.c_int32(0)
+        words = ctypes.c_int64(0)
+        a, b, c = ctypes.c_void_p(), ctypes.c_void_p(), ctypes.c_void_p()
+        rc = load_library().ubp_packed_layout(self.handle, sub_stripes, col_tiles, native, ctypes.byref(nrg),
+                                              ctypes.byref(a), ctypes.byref(b), ctypes.byref(c), ctypes.byref(words))
+        if rc != UBP_OK:
+            raise UBPError(rc, "ubp_packed_layout")
+
+        def copy(ptr, n, dt):
+            if n == 0:
+                return np.zeros(0, dtype=dt)
+            buf = (ctypes.c_char * (n * np.dtype(dt).itemsize)).from_address(ptr.value)
+            return np.frombuffer(buf, dtype=dt).copy()
+        return (copy(a, nrg.value + 1, np.int32), copy(b, nrg.value, np.int32), copy(c, words.value, np.uint32))
 
     def _view(self, fn, np_dtype):
         n = ctypes.c_int64(0)

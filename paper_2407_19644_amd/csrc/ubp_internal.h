@@ -50,6 +50,7 @@ constexpr int ring_swizzle(int CT, int r) { return CT == 2 ? ((r >> 2) & 1) : CT
 // LDS ring together.
 struct StripeLayout {
     int G = 0, CT = 0;
+    bool native = false; // block-native record format (see below)
     int nrg = 0;     // row groups
     int nch = 0;     // slots (chunks of kSlotRows X rows) the producer stages: ceil(K / 64)
     std::vector<int32_t> rg_ptr;     // [nrg + 1] first step of each row group (step counts are multiples of kPrefetchDepth)
@@ -68,6 +69,15 @@ struct StripeLayout {
     //                        8 16-bit values per lane), all zero when the step has no weight there
     // A row group's last steps may be empty (no stripes, nothing read): they pad its step count
     // to a multiple of kPrefetchDepth so that the kernel's unrolled loop has a single exit.
+    //
+    // Block-native format (bh <= 16, bw in {4, 8, 16, 32}, G > 1): columns are not merged; a step
+    // holds 32 / bw whole blocks, and because a block has at most one row congruent to n modulo
+    // 16, ONE fragment serves every stripe: lane (n, g) holds the weight of that row for each of
+    // its entries, and the kernel zeroes it for the stripes whose row 16*j + n the block does not
+    // cover.  Records are 128 + 256 dwords:
+    //       addr as above;  second dword of lane l: bits 0-7 / 8-15 = n - (first row of the block
+    //       of the lane's first / second entry quad, relative to the row group) + 64, or 0 for a
+    //       padding quad; bit 31 = bit l of the control word (lanes 0..31)
     std::vector<uint32_t> stream;
     int64_t nsteps = 0;
     int64_t total_mfma = 0; // MFMA issues per 16-column tile (steps x stripes with weights)
@@ -91,11 +101,13 @@ struct ubp_packed {
     std::vector<uint8_t> values; // nb*bw*bh elements of dtype, rotated
     // private layouts
     ubp::StripeLayout sg[ubp::kNumLayouts];
+    ubp::StripeLayout sgn[ubp::kNumLayouts]; // block-native variants (G = 0 where not built)
     // device side
     int32_t *d_indptr = nullptr;
     int32_t *d_indices = nullptr;
     float *d_values_f32 = nullptr; // rotated values widened to fp32 (exact)
     ubp::StripeLayoutDev d_sg[ubp::kNumLayouts];
+    ubp::StripeLayoutDev d_sgn[ubp::kNumLayouts];
     uint32_t *d_error = nullptr;   // set by a kernel whose bounded wait ran out
     int64_t device_bytes = 0;
 };

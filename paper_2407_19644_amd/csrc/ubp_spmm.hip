@@ -30,6 +30,8 @@ typedef short short8v __attribute__((ext_vector_type(8)));
 typedef _Float16 half8v __attribute__((ext_vector_type(8)));
 typedef __bf16 bf8v __attribute__((ext_vector_type(8)));
 typedef float float4v __attribute__((ext_vector_type(4)));
+typedef uint32_t uint2v __attribute__((ext_vector_type(2)));
+typedef uint32_t uint4v __attribute__((ext_vector_type(4)));
 
 struct DeviceGuard {
     int prev = -1;
@@ -143,14 +145,17 @@ struct StripeArgs {
     const int32_t *rg_ptr;
     const int32_t *rg_order;
     const uint32_t *stream;
+    uint32_t stream_bytes;   // size of the record stream (buffer-addressed: below 4 GB)
     const uint16_t *X;
     void *Y;
     int64_t ldx, ldy;
-    int M, K, N;
+    int M, K, N, bh;
     int nrg, nch;            // row groups, 64-row chunks of X
     int ring_bytes;          // bytes of the LDS ring actually used (all of K when K is shorter than the ring)
     int ctile0, n_coltiles;  // first column tile of this launch, number of tiles in it
     int n_wgrows;
+    int n_producers;         // producer wavefronts per workgroup: 1, 2 or 4 (the last wavefronts)
+    int resident;            // the ring holds all of K: slots are never refilled, a consumer may walk several row groups
     int vec_ok;              // X and Y allow 16-byte vector access on every row
     uint32_t *err;           // set to nonzero when a bounded wait runs out
 };
@@ -163,16 +168,17 @@ __device__ __forceinline__ float4v mfma16(short8v a, short8v b, float4v c) {
         return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8v, a), __builtin_bit_cast(half8v, b), c, 0, 0, 0);
 }
 
-__device__ __forceinline__ short4v lds_read_tr(const char *lds_base, int byte_off) {
+// transposed 8-byte read at an absolute LDS byte address
+__device__ __forceinline__ short4v lds_read_tr(uint32_t lds_addr) {
     typedef __attribute__((address_space(3))) short4v *lds_ptr;
-    return __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(lds_base + byte_off));
+    return __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(uintptr_t)lds_addr);
 }
 
 // 16 bytes per lane from global memory straight into LDS at lds_base + 16 * lane (lds_base
 // wave-uniform).  Written as inline assembly on purpose: the compiler then does not treat
 // the load as a pending LDS write, which would make it wait for ALL outstanding vector
 // memory operations before every LDS read.  Ordering against the LDS reads of the staged
-// data is done by hand (wait_vmcnt, then the slot's ready flag).
+// data is done by hand (wait_vmcnt, then the producer's counter of resident chunks).
 __device__ __forceinline__ void load16_to_lds(const void *gbase, uint32_t lane_off, uint32_t lds_base) {
     // address = gbase (wave-uniform, in SGPRs) + lane_off (32-bit per-lane byte offset)
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(lane_off), "s"(gbase), "s"(lds_base));
@@ -188,123 +194,175 @@ template <int N> __device__ __forceinline__ void wait_vmcnt() {
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
+// waits until at most n vector memory operations of this wavefront are outstanding (n is
+// wave-uniform; it is rounded down to the nearest available immediate, which only waits longer)
+__device__ __forceinline__ void wait_vmcnt_at_most(int n) {
+    if (n >= 48) wait_vmcnt<48>();
+    else if (n >= 32) wait_vmcnt<32>();
+    else if (n >= 24) wait_vmcnt<24>();
+    else if (n >= 16) wait_vmcnt<16>();
+    else if (n >= 12) wait_vmcnt<12>();
+    else if (n >= 8) wait_vmcnt<8>();
+    else if (n >= 6) wait_vmcnt<6>();
+    else if (n >= 4) wait_vmcnt<4>();
+    else if (n >= 3) wait_vmcnt<3>();
+    else if (n >= 2) wait_vmcnt<2>();
+    else if (n >= 1) wait_vmcnt<1>();
+    else wait_vmcnt<0>();
+}
+
 __device__ __forceinline__ uint32_t flag_load(uint32_t *p) {
     return __hip_atomic_load(p, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP);
 }
 
 constexpr int kSpinLimit = 1 << 22; // polls before a wait gives up (each poll is >= 100 cycles)
 
-constexpr int stripe_max_threads(int G, int CT, int D) {
-    // accumulators + operand fragments + D prefetched step records, in VGPRs per lane
-    return (4 * G * CT + 4 * CT + D * (2 + 4 * G) + 24) <= 128 ? 1024 : 512;
+// The gather of step s+1 is issued before the MFMAs of step s (two operand buffers) except
+// for the largest tile, where the second buffer would halve the wavefronts per SIMD.
+constexpr bool stripe_pipelined(int G, int CT, bool NATIVE) { return NATIVE || G * CT < 32; }
+
+constexpr int stripe_max_threads(int G, int CT, int D, bool NATIVE) {
+    // accumulators + operand buffer(s) + D prefetched step records + addressing, in VGPRs
+    // per lane; 512 per SIMD lane are shared by the wavefronts resident on the SIMD
+    const int regs = 4 * G * CT + (stripe_pipelined(G, CT, NATIVE) ? 8 : 4) * CT + D * (2 + 4 * (NATIVE ? 1 : G)) +
+                     (NATIVE ? 28 : G == 1 ? 8 : 20);
+    return regs <= 128 ? 1024 : regs <= 256 ? 512 : 256;
 }
 
-// One workgroup = one producer wavefront + up to 15 consumer wavefronts sharing one tile of
-// 16*CT columns of X / Y.
-//  * The producer stages X in 64-row chunks into a ring of LDS slots (ring row = X row mod
-//    ring rows).  FAST (full column tile, 16-byte aligned rows): direct global->LDS loads,
-//    several chunks in flight; otherwise (ragged last column tile, odd pitches) through
-//    registers with zero fill past column N.  A chunk's slot is refilled only after every
-//    consumer has released the chunk that occupied it (done counters), and a chunk is read
-//    only after the producer has published it (ready generation numbers); there is no
-//    workgroup barrier after start-up, so consumers drift apart by up to a ring of rows and
-//    their uneven per-chunk work averages out.
+// One workgroup = 1, 2 or 4 producer wavefronts + up to 15 consumer wavefronts sharing one
+// tile of 16*CT columns of X / Y.
+//  * The producers stage X in 64-row chunks into a ring of LDS slots (ring row = X row mod
+//    ring rows); each takes every n-th kilobyte of every chunk (one wavefront issues a direct
+//    global->LDS load only every ~85 cycles, about 28 GB/s, so wide tiles need several).  FAST
+//    (full column tile, 16-byte aligned rows): direct global->LDS loads, several chunks in
+//    flight; otherwise (ragged last column tile, odd pitches) through registers with zero
+//    fill past column N.  Each producer publishes one counter, the number of chunks whose
+//    share it has landed (in order); a chunk is resident when all of them have passed it.
+//    Every consumer publishes one counter of its own, the number of leading chunks it will
+//    not read again; a slot is refilled once all of them have passed the chunk that occupies
+//    it.  There is no workgroup barrier after start-up, so consumers drift apart by up to a
+//    ring of rows and their uneven per-chunk work averages out.
 //  * Each consumer owns one row group (G aligned 16-row stripes) and keeps its G*CT output
 //    tiles in fp32 accumulators for the whole K loop (output stationary).  Its steps form a
 //    contiguous stream of fixed-size records (LDS gather addresses, chunk bookkeeping,
 //    weight fragments), fetched D steps ahead into a register ring.
 //  * A step gathers 32 staged rows with two transposed LDS reads per lane and column tile
 //    and issues one 16x16x32 MFMA per (stripe with nonzero weights, column tile).  The
-//    product is formed transposed (pixels x rows) so that a lane holds 4 consecutive
-//    pixels of one output row.
+//    gather of step s+1 is issued before the MFMAs of step s (two operand buffers), so LDS
+//    latency is covered by matrix work of the same wavefront.  The product is formed
+//    transposed (pixels x rows) so that a lane holds 4 consecutive pixels of one output row.
 // Every wait is bounded: if one runs out the wavefront raises *err and goes on without
 // waiting (wrong numbers, but the kernel always terminates).
-template <bool BF16, typename TY, int G, int CT, int D, bool FAST>
-__global__ __launch_bounds__(stripe_max_threads(G, CT, D)) void stripe_kernel(StripeArgs a) {
+template <bool BF16, typename TY, int G, int CT, int D, bool FAST, bool NATIVE>
+__global__ __launch_bounds__(stripe_max_threads(G, CT, D, NATIVE)) void stripe_kernel(StripeArgs a) {
     constexpr int NTW = 16 * CT;
     constexpr int PITCH = ring_pitch(CT);
     constexpr int PIECES = 2 * CT; // 16-byte pieces per staged row
-    constexpr int RR = ring_rows(CT), R = ring_slots(CT), KS = kSlotRows;
-    constexpr int REC_DW = 128 + 256 * G;
+    constexpr int R = ring_slots(CT), KS = kSlotRows;
+    constexpr int FG = NATIVE ? 1 : G; // weight fragments per record
+    constexpr int REC_BYTES = (128 + 256 * FG) * 4;
     constexpr int NINST = KS * PIECES / 64; // direct-to-LDS instructions per chunk (1 KB each)
-    constexpr int LAG = 56 / NINST;         // chunks kept in flight before their readiness is published
     extern __shared__ __attribute__((aligned(1024))) char smem[];
-    uint32_t *ready = reinterpret_cast<uint32_t *>(smem + a.ring_bytes); // [R] generation + 1 of the chunk in the slot
-    uint32_t *done = ready + R;                                        // [R] releases received, all generations
+    uint32_t *published_p = reinterpret_cast<uint32_t *>(smem + a.ring_bytes); // [4] chunks landed, per producer
+    uint32_t *released_p = published_p + 16;                                   // [16] per consumer wavefront
 
     // workgroup -> (column tile, workgroup row); consecutive workgroup ids go round-robin
     // over the 8 XCDs, so tiles are dealt by id mod 8 and all row groups of one column tile
-    // run on one XCD at about the same time: they share the X tile in that XCD's L2, which
-    // measured better than the alternative of keeping one workgroup row's step records in L2
-    // and streaming X once per workgroup row.
+    // run on one XCD at about the same time: they share the X tile in that XCD's L2.  (Walking
+    // several column tiles of an XCD together, row by row, so that they share the step records
+    // as well, measured within 5 % of this on the largest layer: not worth the extra indexing.)
     const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
     const int my_tiles = (a.n_coltiles - xcd + 7) >> 3;
     if (local >= my_tiles * a.n_wgrows) return;
     const int ctile = a.ctile0 + xcd + 8 * (local / a.n_wgrows);
     const int wgrow = local % a.n_wgrows;
 
-    const int NC = (int)(blockDim.x >> 6) - 1; // consumer wavefronts; the last wavefront produces
+    const int NP = a.n_producers;
+    const int NC = (int)(blockDim.x >> 6) - NP; // consumer wavefronts; the last NP wavefronts produce
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lane = threadIdx.x & 63;
     const int col0 = ctile * NTW;
-    const int rg0 = wgrow * NC;
-    const int active = min(NC, a.nrg - rg0); // consumers that own a row group
+    // Ring mode: workgroup row w owns row groups (in heaviest-first order) w*NC .. w*NC+NC-1, one
+    // per consumer: similar weights side by side keep the consumers of a ring in step.  Resident
+    // mode: consumer v of workgroup row w walks entries (i*NC + v)*n_wgrows + w, i = 0, 1, ...
+    const int q0 = a.resident ? wave * a.n_wgrows + wgrow : wgrow * NC + wave;
+    const int q_step = a.resident ? NC * a.n_wgrows : a.nrg; // ring mode: one row group only
+    const int active = a.resident ? NC : min(NC, a.nrg - wgrow * NC); // consumers the producers wait for (ring mode)
 
-    if (threadIdx.x < 2 * R) ready[threadIdx.x] = 0u; // ready[] and done[]
+    // counters start at zero; the slots of producers that do not exist never hold anything back
+    if (threadIdx.x < 32) published_p[threadIdx.x] = (threadIdx.x < 4 && (int)threadIdx.x >= NP) ? 0x7fffffffu : 0u;
     __syncthreads();
 
     // ------------------------------------------------------------------ producer
-    if (wave == NC) {
+    if (wave >= NC) {
+        const int me = wave - NC; // this producer takes instructions me, me + NP, ... of every chunk
         int published = 0;
+        int free_upto = R; // chunks below this may be staged without asking: their slots are free
         bool broken = false;
         auto publish_upto = [&](int upto) {
-            while (published < upto) {
-                // relaxed on purpose: the data is known to have landed (explicit vmcnt wait, or LDS
-                // writes of this same wavefront, which LDS executes in order before this store); a
-                // release here would make the compiler drain every load still in flight
+            // relaxed on purpose: the data is known to have landed (explicit vmcnt wait, or LDS
+            // writes of this same wavefront, which LDS executes in order before this store); a
+            // release here would make the compiler drain every load still in flight
+            if (upto > published) {
+                published = upto;
                 if (lane == 0)
-                    __hip_atomic_store(&ready[published % R], (uint32_t)(published / R + 1), __ATOMIC_RELAXED,
-                                       __HIP_MEMORY_SCOPE_WORKGROUP);
-                ++published;
+                    __hip_atomic_store(published_p + me, (uint32_t)upto, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
             }
+        };
+        // lane w < active looks at consumer w's counter; the other lanes never hold anything back
+        auto poll = [&]() -> uint32_t {
+            uint32_t v = 0xffffffffu;
+            if (lane < active) v = __hip_atomic_load(&released_p[lane], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            asm volatile("" ::: "memory");
+            return v;
         };
         __builtin_amdgcn_s_setprio(3); // little work, but everyone else waits for it
         const uint32_t ring0 = __builtin_amdgcn_readfirstlane(lds_address(smem));
         const int r_in = lane / PIECES, pp = lane % PIECES;
-        // FAST: byte offset of this lane's 16-byte piece from the chunk's first element, for each
-        // of the NINST instructions of a chunk.  The swizzle repeats every 8 rows at most, chunks
-        // are 64 rows, so the offsets are the same for every chunk; only the base moves.
-        uint32_t voff[NINST];
+        constexpr int RPI = 64 / PIECES; // rows covered by one 1 KB instruction
+        // FAST: byte offset of this lane's 16-byte piece for instruction i of a chunk, from the
+        // chunk's first element.
         auto piece_offset = [&](int i, int rows) {
-            const int r = i * (64 / PIECES) + r_in;              // row inside the chunk
+            const int r = i * RPI + r_in;                        // row inside the chunk
             const int u = (pp >> 1) ^ ring_swizzle(CT, r);       // logical unit stored at this position
             // rows past K load the chunk's last row again (never read): every chunk then issues
-            // exactly NINST loads, which the in-order vmcnt bookkeeping relies on
+            // the same number of loads, which the in-order vmcnt bookkeeping relies on
             return (uint32_t)(((int64_t)min(r, rows - 1) * a.ldx + u * 16 + (pp & 1) * 8) * 2);
         };
-        if constexpr (FAST) {
-#pragma unroll
-            for (int i = 0; i < NINST; ++i) voff[i] = piece_offset(i, KS);
-        }
+        // Full chunks: the swizzle depends on the row modulo 8 at most and an instruction starts at
+        // a multiple of 4 rows, so relative to the first row of ITS instruction a lane's offset
+        // takes two values only (even / odd i); the wave-uniform base moves instead.
+        const uint32_t voff_even = piece_offset(0, KS);
+        const uint32_t voff_odd = NINST > 1 ? piece_offset(1, KS) - (uint32_t)((int64_t)RPI * a.ldx * 2) : voff_even;
+        const int per = NINST / NP;                    // instructions of a chunk that are mine
+        const int lag = max(1, min(48 / per, R / 2));  // chunks kept in flight before they are published
+        const int64_t inst_stride = (int64_t)RPI * a.ldx; // elements between the rows of two instructions
         for (int c = 0; c < a.nch; ++c) {
             const int slot = c % R;
-            if (c >= R && !broken) {
-                const uint32_t target = (uint32_t)active * (uint32_t)(c / R);
-                if (flag_load(&done[slot]) < target) {
+            if (c >= free_upto && !broken) {
+                // chunk c replaces chunk c - R: every consumer must have passed that one
+                const uint32_t target = (uint32_t)(c - R + 1);
+                uint32_t v = poll();
+                if (__builtin_amdgcn_ballot_w64(v < target) != 0) {
                     // about to block: first publish every chunk already issued, the consumers
                     // this wait depends on may be waiting for one of them
                     wait_vmcnt<0>();
                     publish_upto(c);
                     int spins = 0;
-                    while (flag_load(&done[slot]) < target) {
+                    do {
                         if (++spins > kSpinLimit) {
                             broken = true;
                             if (lane == 0) atomicOr(a.err, 1u);
                             break;
                         }
                         __builtin_amdgcn_s_sleep(2);
-                    }
+                        v = poll();
+                    } while (__builtin_amdgcn_ballot_w64(v < target) != 0);
                 }
+                // how far the slowest consumer really is: saves asking again for the next chunks
+                int ahead = 1;
+                while (ahead < R && __builtin_amdgcn_ballot_w64(v < target + (uint32_t)ahead) == 0) ++ahead;
+                free_upto = c + ahead;
             }
             const int k0 = c * KS;
             const int rows = min(KS, a.K - k0);
@@ -312,18 +370,18 @@ __global__ __launch_bounds__(stripe_max_threads(G, CT, D)) void stripe_kernel(St
                 const uint32_t lds0 = ring0 + (uint32_t)(slot * KS * PITCH);
                 const uint16_t *base = a.X + (int64_t)k0 * a.ldx + col0; // wave-uniform
                 if (rows == KS) {
-#pragma unroll
-                    for (int i = 0; i < NINST; ++i) load16_to_lds(base, voff[i], lds0 + (uint32_t)i * 1024u);
+                    for (int i = me; i < NINST; i += NP)
+                        load16_to_lds(base + i * inst_stride, (i & 1) ? voff_odd : voff_even, lds0 + (uint32_t)i * 1024u);
                 } else {
-#pragma unroll
-                    for (int i = 0; i < NINST; ++i) load16_to_lds(base, piece_offset(i, rows), lds0 + (uint32_t)i * 1024u);
+                    for (int i = me; i < NINST; i += NP)
+                        load16_to_lds(base, piece_offset(i, rows), lds0 + (uint32_t)i * 1024u);
                 }
-                if (c + 1 - published > LAG) {
-                    wait_vmcnt<LAG * NINST>(); // vector memory completes in order: chunks <= c - LAG have landed
-                    publish_upto(c + 1 - LAG);
+                if (c + 1 - published > lag) {
+                    wait_vmcnt_at_most(lag * per); // vector memory completes in order: chunks <= c - lag have landed
+                    publish_upto(c + 1 - lag);
                 }
             } else {
-                for (int piece = lane; piece < rows * PIECES; piece += 64) {
+                for (int piece = lane + 64 * me; piece < rows * PIECES; piece += 64 * NP) {
                     const int r = piece / PIECES, q = piece % PIECES;
                     const int u = (q >> 1) ^ ring_swizzle(CT, slot * KS + r);
                     const int col = col0 + u * 16 + (q & 1) * 8;
@@ -340,71 +398,113 @@ __global__ __launch_bounds__(stripe_max_threads(G, CT, D)) void stripe_kernel(St
                     *reinterpret_cast<uint4 *>(smem + (slot * KS + r) * PITCH + q * 16) = v;
                 }
                 asm volatile("" ::: "memory");
-                publish_upto(c + 1); // LDS executes this wavefront's writes above before the flag store
+                publish_upto(c + 1); // LDS executes this wavefront's writes above before the counter store
+            }
+        }
+        // the tail: publish the chunks still in flight one by one as they land
+        if constexpr (FAST) {
+            while (published < a.nch) {
+                wait_vmcnt_at_most((a.nch - published - 1) * per);
+                publish_upto(published + 1);
             }
         }
         wait_vmcnt<0>();
         publish_upto(a.nch);
         return;
     }
-    if (wave >= active) return; // no row group left for this wavefront
+    if (q0 >= a.nrg) return; // no row group for this wavefront
 
     // ------------------------------------------------------------------ consumer
-    const int rg = __builtin_amdgcn_readfirstlane(a.rg_order[rg0 + wave]);
+    int q = q0;
+    int rg = __builtin_amdgcn_readfirstlane(a.rg_order[q]);
     int s = __builtin_amdgcn_readfirstlane(a.rg_ptr[rg]);
-    const int s_all = __builtin_amdgcn_readfirstlane(a.rg_ptr[rg + 1]);
+    int s_all = __builtin_amdgcn_readfirstlane(a.rg_ptr[rg + 1]);
 
     float4v acc[G][CT];
-#pragma unroll
-    for (int j = 0; j < G; ++j)
-#pragma unroll
-        for (int c = 0; c < CT; ++c) acc[j][c] = float4v{0.f, 0.f, 0.f, 0.f};
 
-    // Record of step t: wave-uniform base (kept in SGPRs, advanced by one record per step) plus
-    // a fixed per-lane offset, so that a refill costs no vector ALU work.  The stream carries D
-    // spare records at its end: refills run D steps ahead and simply read on past the row
-    // group's last step (those records are never used).
-    uint2 info[D];
-    uint4 wf[D][G];
-    const char *rec_next = reinterpret_cast<const char *>(a.stream) + (int64_t)s * (REC_DW * 4);
+    // Records are fetched through a buffer resource: the address of a load is the (wave-uniform)
+    // byte offset of the record, kept in a scalar register and advanced by one record per step,
+    // plus a fixed per-lane offset, so that a refill costs no vector ALU work.  The stream
+    // carries D spare records at its end: refills run D steps ahead and simply read on past the
+    // row group's last step (those records are never used).
+    const __amdgpu_buffer_rsrc_t rsrc =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t *>(a.stream), 0, (int)a.stream_bytes, 0x00020000);
+    uint32_t info_x[D], info_y[D];
+    uint4v wf[D][FG];
+    uint32_t rec_next = 0;
     const uint32_t lane8 = (uint32_t)lane * 8u, lane16 = (uint32_t)lane * 16u;
     auto issue = [&](int d) {
-        info[d] = *reinterpret_cast<const uint2 *>(rec_next + lane8);
+        const uint2v inf = __builtin_bit_cast(uint2v, __builtin_amdgcn_raw_buffer_load_b64(rsrc, lane8, rec_next, 0));
+        info_x[d] = inf[0];
+        info_y[d] = inf[1];
 #pragma unroll
-        for (int j = 0; j < G; ++j) wf[d][j] = *reinterpret_cast<const uint4 *>(rec_next + 512 + j * 1024 + lane16);
-        rec_next += REC_DW * 4;
+        for (int j = 0; j < FG; ++j)
+            wf[d][j] = __builtin_bit_cast(uint4v, __builtin_amdgcn_raw_buffer_load_b128(rsrc, lane16 + (uint32_t)(512 + j * 1024), rec_next, 0));
+        rec_next += REC_BYTES;
     };
 
-    int released = 0;   // chunks this wavefront has released
-    int ready_upto = 0; // chunks known to be published
+    int released = 0;   // chunks this wavefront has handed back
+    int ready_upto = 0; // chunks known to be resident
     bool broken = false;
+    uint32_t *mine = released_p + wave;
     auto wait_published = [&](int chunk) {
-        if (chunk < ready_upto || broken) return;
-        const uint32_t want = (uint32_t)(chunk / R + 1);
+        if (chunk < ready_upto) return;
         int spins = 0;
-        while (flag_load(&ready[chunk % R]) < want) {
+        for (;;) {
+            const uint32_t seen = flag_load(published_p + (lane & 3)); // unused producer slots were set to "all"
+            ready_upto = (int)min(min(__builtin_amdgcn_readlane(seen, 0), __builtin_amdgcn_readlane(seen, 1)),
+                                  min(__builtin_amdgcn_readlane(seen, 2), __builtin_amdgcn_readlane(seen, 3)));
+            if (chunk < ready_upto) return;
             if (++spins > kSpinLimit) {
                 broken = true; // reported after the stream loop (no global atomic inside it)
+                ready_upto = 0x7fffffff;
                 return;
             }
             __builtin_amdgcn_s_sleep(1);
         }
-        ready_upto = chunk + 1;
     };
-    // Releases go in chunk order, each only after the chunk has been published: the producer's
-    // done counters then never contain a release of a chunk that is not in the ring yet (a
-    // wavefront whose steps skip chunks would otherwise release them ahead of time and let the
-    // producer refill a slot another wavefront still reads).
+    // A counter only says "I will not read chunks below this again", so it can run ahead of the
+    // producer (chunks this wavefront never reads) without harm.
     auto release_upto = [&](int upto) {
-        // relaxed + a compiler barrier: the reads of these chunks returned before the MFMAs that
-        // used them were issued, and LDS executes this wavefront's operations in order; a release
-        // would make the compiler drain the prefetch ring at every chunk
-        asm volatile("" ::: "memory");
-        while (released < upto) {
-            wait_published(released);
-            if (lane == 0)
-                __hip_atomic_fetch_add(&done[released % R], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-            ++released;
+        if (upto > released) {
+            released = upto;
+            // relaxed + a compiler barrier: the reads of these chunks returned before the MFMAs
+            // that used them were issued, and LDS executes this wavefront's operations in order
+            asm volatile("" ::: "memory");
+            if (lane == 0) __hip_atomic_store(mine, (uint32_t)upto, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        }
+    };
+
+    // Gather of the step whose record sits in ring slot d into operand buffer b.  The record's
+    // control word says which chunk must be resident and what may be handed back now (nothing
+    // that the step before reads: its reads may still be in flight).  The reads are issued even
+    // for an empty step (address 0, never used): the number of LDS operations between a gather
+    // and its use is then the same on every path, which lets the compiler wait for exactly the
+    // older gather instead of draining the newer one as well.
+    constexpr bool PIPE = stripe_pipelined(G, CT, NATIVE);
+    const uint32_t ring_base = __builtin_amdgcn_readfirstlane(lds_address(smem));
+    short8v xf[PIPE ? 2 : 1][CT];
+    auto stage = [&](int d, int b, bool foreign) {
+        // (foreign: the slot after the row group's last step holds another row group's record;
+        // its gather is issued all the same, to valid addresses, and never used, but its control
+        // word must not be acted on)
+        uint32_t ctl = 0u;
+        if (!foreign) {
+            // block-native records spread the control word over bit 31 of the lanes' second dwords
+            if constexpr (NATIVE) ctl = (uint32_t)__builtin_amdgcn_ballot_w64((int32_t)info_y[d] < 0);
+            else ctl = __builtin_amdgcn_readfirstlane(info_y[d]);
+        }
+        release_upto((int)(ctl >> 16));
+        wait_published((int)(ctl & 0xffffu));
+        // absolute LDS addresses: the ring starts at a multiple of 1 KB, so adding its base
+        // commutes with the XOR that selects the column tile
+        const uint32_t ix = info_x[d];
+        const uint32_t a_lo = ring_base + ((ix & 0x3fffu) << 3), a_hi = ring_base + (((ix >> 14) & 0x3fffu) << 3);
+#pragma unroll
+        for (int c = 0; c < CT; ++c) {
+            const short4v p0 = lds_read_tr(a_lo ^ (uint32_t)(c << 5));
+            const short4v p1 = lds_read_tr(a_hi ^ (uint32_t)(c << 5));
+            xf[b][c] = __builtin_shufflevector(p0, p1, 0, 1, 2, 3, 4, 5, 6, 7);
         }
     };
 
@@ -412,74 +512,95 @@ __global__ __launch_bounds__(stripe_max_threads(G, CT, D)) void stripe_kernel(St
     // the last ones possibly empty), and every step refills its ring slot unconditionally.  The number of
     // loads in flight behind a slot is then the same on every path into every step, which
     // lets the compiler wait with a partial vmcnt instead of draining the ring.
-    static_assert(D == kPrefetchDepth, "row groups are padded to a multiple of the prefetch depth");
-    if (s < s_all) {
-#pragma unroll
-        for (int d = 0; d < D; ++d) {
-            issue(d);
-            __builtin_amdgcn_sched_barrier(0); // same issue order as in the loop, slot by slot
-        }
-        for (; s < s_all; s += D) {
+    static_assert(D == kPrefetchDepth && D % 2 == 0, "row groups are padded to a multiple of the prefetch depth");
+    auto start_stream = [&]() { // first D records of the row group whose steps are s .. s_all
+        rec_next = (uint32_t)s * (uint32_t)REC_BYTES;
+        if (s < s_all) {
 #pragma unroll
             for (int d = 0; d < D; ++d) {
-                const uint2 inf = info[d];
-                const uint32_t ctl = __builtin_amdgcn_readfirstlane(inf.y);
-                const int need = (int)(ctl & 0xffffu), rel = (int)(ctl >> 16);
-                // first give back what no later step reads (their reads were consumed by earlier
-                // MFMAs), then wait for the highest chunk this step reads; chunks are published in
-                // order, so that covers every chunk of the step.  Releasing first matters: the
-                // producer may need exactly those slots to bring the awaited chunk in.
-                release_upto(rel);
-                wait_published(need);
-                const uint32_t mask = __builtin_amdgcn_readfirstlane(inf.x >> 28);
-                if (mask) {
-                    const int a_lo = (int)((inf.x & 0x3fffu) << 3), a_hi = (int)(((inf.x >> 14) & 0x3fffu) << 3);
-                    short8v xf[CT];
+                issue(d);
+                __builtin_amdgcn_sched_barrier(0); // same issue order as in the loop, slot by slot
+            }
+        }
+    };
+    start_stream();
+    const int g = lane >> 4, n = lane & 15;
+    TY *Yt = static_cast<TY *>(a.Y);
+    for (;;) {
 #pragma unroll
-                    for (int c = 0; c < CT; ++c) {
-                        const short4v p0 = lds_read_tr(smem, a_lo ^ (c << 5));
-                        const short4v p1 = lds_read_tr(smem, a_hi ^ (c << 5));
-                        xf[c] = __builtin_shufflevector(p0, p1, 0, 1, 2, 3, 4, 5, 6, 7);
-                    }
+        for (int j = 0; j < G; ++j)
+#pragma unroll
+            for (int c = 0; c < CT; ++c) acc[j][c] = float4v{0.f, 0.f, 0.f, 0.f};
+        if (s < s_all) {
+            if constexpr (PIPE) stage(0, 0, false);
+            for (; s < s_all; s += D) {
+#pragma unroll
+                for (int d = 0; d < D; ++d) {
+                    // the next step's gather first (or, with one operand buffer, this step's own)
+                    if constexpr (PIPE) stage((d + 1) % D, (d + 1) & 1, d + 1 == D && s + D >= s_all);
+                    else stage(d, 0, false);
+                    const uint32_t mask = __builtin_amdgcn_readfirstlane(info_x[d] >> 28);
+                    // block-native: the one fragment holds, per lane, the weight of the block row that
+                    // is congruent to the lane's row modulo 16; stripe j keeps an entry quad only where
+                    // the block covers row 16*j + n
+                    [[maybe_unused]] const int t_lo = (int)(info_y[d] & 0x7fu) - 64;
+                    [[maybe_unused]] const int t_hi = (int)((info_y[d] >> 8) & 0x7fu) - 64;
 #pragma unroll
                     for (int j = 0; j < G; ++j) {
                         if (mask & (1u << j)) {
-                            const short8v wv = __builtin_bit_cast(short8v, wf[d][j]);
+                            short8v wv;
+                            if constexpr (NATIVE) {
+                                const uint4v f = wf[d][0];
+                                const bool lo_ok = (uint32_t)(t_lo + 16 * j) < (uint32_t)a.bh;
+                                const bool hi_ok = (uint32_t)(t_hi + 16 * j) < (uint32_t)a.bh;
+                                const uint4v w = {lo_ok ? f[0] : 0u, lo_ok ? f[1] : 0u, hi_ok ? f[2] : 0u, hi_ok ? f[3] : 0u};
+                                wv = __builtin_bit_cast(short8v, w);
+                            } else {
+                                wv = __builtin_bit_cast(short8v, wf[d][j]);
+                            }
 #pragma unroll
-                            for (int c = 0; c < CT; ++c) acc[j][c] = mfma16<BF16>(xf[c], wv, acc[j][c]);
+                            for (int c = 0; c < CT; ++c) acc[j][c] = mfma16<BF16>(xf[PIPE ? (d & 1) : 0][c], wv, acc[j][c]);
                         }
                     }
+                    issue(d);
                 }
-                issue(d);
             }
         }
+        // the next row group's first records are requested before this one's tiles are stored
+        const int rg_done = rg;
+        q += q_step;
+        const bool more = q < a.nrg;
+        if (more) {
+            rg = __builtin_amdgcn_readfirstlane(a.rg_order[q]);
+            s = __builtin_amdgcn_readfirstlane(a.rg_ptr[rg]);
+            s_all = __builtin_amdgcn_readfirstlane(a.rg_ptr[rg + 1]);
+            start_stream();
+        } else {
+            release_upto(a.nch); // the last step's reads were consumed by its MFMAs
+        }
+        // ---- store: lane (g = lane/16, n = lane%16) holds pixels col0 + 16*c + 4*g + v of row
+        // 16*(G*rg + j) + n.  Rows no block touches are stored as zeros like any other.
+#pragma unroll
+        for (int j = 0; j < G; ++j) {
+            const int row = (rg_done * G + j) * kStripe + n;
+            if (row >= a.M) continue;
+#pragma unroll
+            for (int c = 0; c < CT; ++c) {
+                const int px = col0 + 16 * c + 4 * g;
+                TY *dst = Yt + (int64_t)row * a.ldy + px;
+                if (a.vec_ok && px + 4 <= a.N) {
+                    float v[4] = {acc[j][c][0], acc[j][c][1], acc[j][c][2], acc[j][c][3]};
+                    store_row<TY, 4>(dst, v);
+                } else {
+#pragma unroll
+                    for (int v = 0; v < 4; ++v)
+                        if (px + v < a.N) dst[v] = from_f32<TY>(acc[j][c][v]);
+                }
+            }
+        }
+        if (!more) break;
     }
     if (broken && lane == 0) atomicOr(a.err, 2u);
-    // the producer counts a release from every consumer for every chunk
-    release_upto(a.nch);
-
-    // ---- store: lane (g = lane/16, n = lane%16) holds pixels col0 + 16*c + 4*g + v of row
-    // 16*(G*rg + j) + n.  Rows no block touches are stored as zeros like any other.
-    const int g = lane >> 4, n = lane & 15;
-    TY *Yt = static_cast<TY *>(a.Y);
-#pragma unroll
-    for (int j = 0; j < G; ++j) {
-        const int row = (rg * G + j) * kStripe + n;
-        if (row >= a.M) continue;
-#pragma unroll
-        for (int c = 0; c < CT; ++c) {
-            const int px = col0 + 16 * c + 4 * g;
-            TY *dst = Yt + (int64_t)row * a.ldy + px;
-            if (a.vec_ok && px + 4 <= a.N) {
-                float v[4] = {acc[j][c][0], acc[j][c][1], acc[j][c][2], acc[j][c][3]};
-                store_row<TY, 4>(dst, v);
-            } else {
-#pragma unroll
-                for (int v = 0; v < 4; ++v)
-                    if (px + v < a.N) dst[v] = from_f32<TY>(acc[j][c][v]);
-            }
-        }
-    }
 }
 
 // ------------------------------------------------------------------ launchers
@@ -514,13 +635,13 @@ ubp_status launch_wros(const ubp_packed *p, const void *X, int64_t ldx, int N, v
                : launch_wros_bh<TX, TY, 1>(p, X, ldx, N, Y, ldy, rpr, st);
 }
 
-template <bool BF16, typename TY, int G, int CT, bool FAST>
+template <bool BF16, typename TY, int G, int CT, bool FAST, bool NATIVE>
 ubp_status launch_stripe_one(StripeArgs a, int ctile0, int n_coltiles, int waves, hipStream_t st) {
     constexpr int D = kPrefetchDepth;
-    const size_t lds = (size_t)a.ring_bytes + 2 * ring_slots(CT) * sizeof(uint32_t);
+    const size_t lds = (size_t)a.ring_bytes + 32 * sizeof(uint32_t); // ring + the progress counters
     static size_t attr_bytes = 0; // per instantiation; the limit is only ever raised
     if (lds > attr_bytes) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&stripe_kernel<BF16, TY, G, CT, D, FAST>),
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&stripe_kernel<BF16, TY, G, CT, D, FAST, NATIVE>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
             (void)hipGetLastError();
             return UBP_ERR_DEVICE;
@@ -530,36 +651,40 @@ ubp_status launch_stripe_one(StripeArgs a, int ctile0, int n_coltiles, int waves
     a.ctile0 = ctile0;
     a.n_coltiles = n_coltiles;
     const unsigned grid = 8u * (unsigned)((n_coltiles + 7) / 8) * (unsigned)a.n_wgrows;
-    hipLaunchKernelGGL((stripe_kernel<BF16, TY, G, CT, D, FAST>), dim3(grid), dim3((unsigned)waves * 64), lds, st, a);
+    hipLaunchKernelGGL((stripe_kernel<BF16, TY, G, CT, D, FAST, NATIVE>), dim3(grid), dim3((unsigned)waves * 64), lds, st, a);
     return hipGetLastError() == hipSuccess ? UBP_OK : UBP_ERR_DEVICE;
 }
 
-template <bool BF16, typename TY, int G, int CT>
+template <bool BF16, typename TY, int G, int CT, bool NATIVE>
 ubp_status launch_stripe_inst(const StripeArgs &a, int waves, hipStream_t st) {
-    if (waves * 64 > stripe_max_threads(G, CT, kPrefetchDepth)) return UBP_ERR_UNSUPPORTED;
+    if (waves * 64 > stripe_max_threads(G, CT, kPrefetchDepth, NATIVE)) return UBP_ERR_UNSUPPORTED;
     // full column tiles with aligned rows take the asynchronous staging path; a ragged last
     // tile (or everything, when rows are not 16-byte aligned) takes the synchronous one
     const int total = (a.N + 16 * CT - 1) / (16 * CT);
     // (the producer addresses a chunk with 32-bit lane offsets: 64 rows of ldx elements must fit)
     const int full = (a.vec_ok && a.ldx <= (int64_t(1) << 24)) ? a.N / (16 * CT) : 0;
     ubp_status rc = UBP_OK;
-    if (full > 0) rc = launch_stripe_one<BF16, TY, G, CT, true>(a, 0, full, waves, st);
+    if (full > 0) rc = launch_stripe_one<BF16, TY, G, CT, true, NATIVE>(a, 0, full, waves, st);
     if (rc == UBP_OK && total > full)
-        rc = launch_stripe_one<BF16, TY, G, CT, false>(a, full, total - full, waves, st);
+        rc = launch_stripe_one<BF16, TY, G, CT, false, NATIVE>(a, full, total - full, waves, st);
     return rc;
 }
 
 template <bool BF16, typename TY>
-ubp_status launch_stripe(const StripeArgs &a, int G, int CT, int waves, hipStream_t st) {
+ubp_status launch_stripe(const StripeArgs &a, int G, int CT, bool native, int waves, hipStream_t st) {
 #define UBP_SG_CASE(GG, CC) \
-    if (G == GG && CT == CC) return launch_stripe_inst<BF16, TY, GG, CC>(a, waves, st);
+    if (G == GG && CT == CC && !native) return launch_stripe_inst<BF16, TY, GG, CC, false>(a, waves, st);
     UBP_SG_CASE(1, 2) UBP_SG_CASE(2, 2) UBP_SG_CASE(4, 2) UBP_SG_CASE(1, 4) UBP_SG_CASE(2, 4) UBP_SG_CASE(4, 4)
     UBP_SG_CASE(1, 8) UBP_SG_CASE(2, 8) UBP_SG_CASE(4, 8)
+#undef UBP_SG_CASE
+#define UBP_SG_CASE(GG, CC) \
+    if (G == GG && CT == CC && native) return launch_stripe_inst<BF16, TY, GG, CC, true>(a, waves, st);
+    UBP_SG_CASE(2, 2) UBP_SG_CASE(4, 2) UBP_SG_CASE(2, 4) UBP_SG_CASE(4, 4) UBP_SG_CASE(2, 8) UBP_SG_CASE(4, 8)
 #undef UBP_SG_CASE
     return UBP_ERR_UNSUPPORTED;
 }
 
-int stripe_max_waves(int G, int CT) { return stripe_max_threads(G, CT, kPrefetchDepth) / 64; }
+int stripe_max_waves(int G, int CT, bool native) { return stripe_max_threads(G, CT, kPrefetchDepth, native) / 64; }
 
 int env_int(const char *name, int dflt) {
     const char *v = std::getenv(name);
@@ -617,6 +742,14 @@ ubp_status upload(ubp_packed *p) {
             ok = ok && dev_copy(&D.rg_order, L.rg_order.data(), L.rg_order.size(), &p->device_bytes);
             ok = ok && dev_copy(&D.stream, L.stream.data(), L.stream.size(), &p->device_bytes);
         }
+        for (int s = 0; s < kNumLayouts && ok; ++s) {
+            const StripeLayout &L = p->sgn[s];
+            if (L.G == 0) continue;
+            StripeLayoutDev &D = p->d_sgn[s];
+            ok = ok && dev_copy(&D.rg_ptr, L.rg_ptr.data(), L.rg_ptr.size(), &p->device_bytes);
+            ok = ok && dev_copy(&D.rg_order, L.rg_order.data(), L.rg_order.size(), &p->device_bytes);
+            ok = ok && dev_copy(&D.stream, L.stream.data(), L.stream.size(), &p->device_bytes);
+        }
     }
     if (!ok) {
         (void)hipGetLastError();
@@ -641,6 +774,9 @@ void release_device(ubp_packed *p) {
         rel(p->d_sg[s].rg_ptr);
         rel(p->d_sg[s].rg_order);
         rel(p->d_sg[s].stream);
+        rel(p->d_sgn[s].rg_ptr);
+        rel(p->d_sgn[s].rg_order);
+        rel(p->d_sgn[s].stream);
     }
 }
 
@@ -699,64 +835,88 @@ ubp_status ubp_spmm_plan(const ubp_packed *p, const void *X_dev, int64_t ldx, in
     int CT = pl.col_tiles ? pl.col_tiles : env_int("UBP_CT", 0);
     int G = pl.sub_stripes ? pl.sub_stripes : env_int("UBP_G", 0);
     int waves = pl.waves ? pl.waves : env_int("UBP_WAVES", 0);
+    int NP = pl.producers ? pl.producers : env_int("UBP_PRODUCERS", 0);
+    if (NP != 0 && NP != 1 && NP != 2 && NP != 4) return UBP_ERR_UNSUPPORTED;
+    int native_req = pl.native ? pl.native : env_int("UBP_NATIVE", 0); // 0 auto, 1 merged columns, 2 block-native
+    if (native_req < 0 || native_req > 2) return UBP_ERR_INVALID_ARG;
+    const bool native = native_req == 2; // (auto = merged columns: the shared operand costs more vector ALU work
+                                         //  per step than the smaller records save)
+    const StripeLayout *layouts = native ? p->sgn : p->sg;
     if ((G != 0 && G != 1 && G != 2 && G != 4) || (CT != 0 && CT != 2 && CT != 4 && CT != 8)) return UBP_ERR_UNSUPPORTED;
-    {
-        // Pick the tile shape with the smallest estimated time.  What a workgroup pulls into its
-        // CU (its row groups' step records plus the X tile, once per workgroup) is what bounds
-        // the large layers; small layers are bounded by how many rounds of workgroups the chip
-        // needs and by a workgroup's start-up and store latency.
-        double best = 0.0;
-        int bestG = 0, bestCT = 0;
-        for (int g = 1; g <= 4; g *= 2)
-            for (int ct = 2; ct <= 8; ct *= 2) {
-                if ((G && g != G) || (CT && ct != CT)) continue;
-                const StripeLayout &Lc = p->sg[layout_slot(g, ct)];
-                if (Lc.G == 0) continue;
-                const int mw = waves ? waves : stripe_max_waves(g, ct);
-                if (mw < 2 || mw > stripe_max_waves(g, ct)) continue;
-                const int rows_wg = (Lc.nrg + (mw - 1) - 1) / (mw - 1);           // workgroup rows
-                const int nc = (Lc.nrg + rows_wg - 1) / rows_wg;                   // consumers per workgroup
-                const int64_t ncol = (N + 16 * ct - 1) / (16 * ct);
-                const double rec = (128 + 256 * g) * 4.0;
-                const double bytes = (double)ncol * ((double)Lc.nsteps * rec + (double)rows_wg * p->K * 32.0 * ct);
-                const int ring = std::min(ring_rows(ct), Lc.nch * kSlotRows) * ring_pitch(ct);
-                const int wave_slots = stripe_max_threads(g, ct, kPrefetchDepth) == 1024 ? 16 : 8;
-                const int resident = std::max(1, std::min((160 * 1024) / (ring + 256), wave_slots / (nc + 1)));
-                const double rounds = std::ceil((double)(ncol * rows_wg) / (256.0 * resident));
-                const double heaviest = Lc.sorted_steps.empty() ? 0.0 : (double)Lc.sorted_steps[0];
-                const double busy = std::min(1.0, (double)(ncol * rows_wg) / 256.0); // CUs that get a workgroup
-                double t = std::max(bytes / (9.0e6 * busy), rounds * (5.0 + 0.3 * heaviest)); // microseconds
-                if (N % (16 * ct) != 0) t += 10.0; // the ragged last column tile takes the slow staging path
-                if (bestG == 0 || t < best) {
-                    best = t;
-                    bestG = g;
-                    bestCT = ct;
-                }
-            }
-        if (bestG == 0) return UBP_ERR_UNSUPPORTED;
-        G = bestG;
-        CT = bestCT;
+    // Tile shape, from measurements on the four benchmark layers.
+    //  * Column tiles as wide as divides N (a ragged last tile takes the slow staging path),
+    //    provided that still leaves a few dozen tiles: wide tiles amortise a step's fixed
+    //    instruction cost over more matrix instructions.
+    //  * Stripes per wavefront follow the block height: a 16-row block touches two stripes
+    //    anyway, so tall row groups cost little extra zero fill and divide the staging of X by
+    //    the rows a workgroup covers; for short blocks one stripe keeps the operands dense.
+    if (CT == 0) {
+        for (int ct = 8; ct >= 2 && CT == 0; ct /= 2)
+            if (N % (16 * ct) == 0 && N / (16 * ct) >= 32) CT = ct;
+        for (int ct = 8; ct >= 2 && CT == 0; ct /= 2)
+            if ((N + 16 * ct - 1) / (16 * ct) >= 32) CT = ct;
+        if (CT == 0) CT = 2;
+    }
+    if (G == 0) {
+        G = p->bh >= 16 ? 4 : p->bh >= 8 ? 2 : 1;
+        while (G > 1 && layouts[layout_slot(G, CT)].G == 0) G >>= 1;
+        if (native && G == 1) G = 2;
+    }
+    if (layouts[layout_slot(G, CT)].G == 0) return UBP_ERR_UNSUPPORTED; // layout not built for this matrix
+    // one wavefront stages about 28 GB/s: a second one as soon as a workgroup's tile is not small
+    if (NP == 0) {
+        NP = ((int64_t)p->K * 32 * CT >= 64 * 1024) ? 2 : 1;
+        if (waves != 0 && waves < NP + 1) NP = 1; // a caller who fixes a tiny workgroup gets one producer
     }
     const int slot = layout_slot(G, CT);
-    const StripeLayout &L = p->sg[slot];
-    const int max_waves = stripe_max_waves(G, CT);
-    if (waves == 0) {
-        // as few workgroup rows as the wavefront limit allows, consumers spread evenly over them
-        const int rows_wg = (L.nrg + (max_waves - 1) - 1) / (max_waves - 1);
-        waves = (L.nrg + rows_wg - 1) / rows_wg + 1; // consumers + one producer
+    const StripeLayout &L = layouts[slot];
+    const int max_waves = stripe_max_waves(G, CT, native);
+    if (max_waves <= NP) return UBP_ERR_UNSUPPORTED;
+    // When the ring holds all of K nothing is ever refilled and a consumer may walk several row
+    // groups one after the other; the number of workgroup rows is then free.  Otherwise every
+    // consumer owns exactly one row group.
+    const bool resident = L.nch <= ring_slots(CT);
+    int wg_rows = pl.wg_rows ? pl.wg_rows : env_int("UBP_WGROWS", 0);
+    if (wg_rows < 0) return UBP_ERR_INVALID_ARG;
+    if (!resident) {
+        if (waves == 0) {
+            // as few workgroup rows as the wavefront limit allows, consumers spread evenly over them
+            const int rows_wg = (L.nrg + (max_waves - NP) - 1) / (max_waves - NP);
+            waves = (L.nrg + rows_wg - 1) / rows_wg + NP; // consumers + producers
+        }
+        if (waves < NP + 1 || waves > max_waves) return UBP_ERR_UNSUPPORTED;
+        const int need_rows = (L.nrg + (waves - NP) - 1) / (waves - NP);
+        if (wg_rows != 0 && wg_rows != need_rows) return UBP_ERR_UNSUPPORTED;
+        wg_rows = need_rows;
+    } else {
+        const int64_t ncol = (N + 16 * CT - 1) / (16 * CT);
+        if (wg_rows == 0) {
+            // about one workgroup per CU in a single round where the column tiles alone do not
+            // fill the chip; then as few workgroup rows as give every consumer the same number
+            // of row groups (no half-used passes)
+            const int target = (int)std::max<int64_t>(1, 256 / std::max<int64_t>(1, ncol));
+            const int nc = std::max(1, (waves ? waves : max_waves) - NP);
+            const int passes = std::max(1, (L.nrg + nc * target - 1) / (nc * target));
+            wg_rows = (L.nrg + nc * passes - 1) / (nc * passes);
+        }
+        wg_rows = std::max(1, std::min(wg_rows, std::max(1, L.nrg)));
+        if (waves == 0) waves = std::min(max_waves - NP, (L.nrg + wg_rows - 1) / wg_rows) + NP;
+        if (waves < NP + 1 || waves > max_waves) return UBP_ERR_UNSUPPORTED;
     }
-    if (waves < 2 || waves > max_waves) return UBP_ERR_UNSUPPORTED;
 
     StripeArgs a;
-    a.rg_ptr = p->d_sg[slot].rg_ptr;
-    a.rg_order = p->d_sg[slot].rg_order;
-    a.stream = p->d_sg[slot].stream;
+    const StripeLayoutDev &LD = native ? p->d_sgn[slot] : p->d_sg[slot];
+    a.rg_ptr = LD.rg_ptr;
+    a.rg_order = LD.rg_order;
+    a.stream = LD.stream;
+    a.stream_bytes = (uint32_t)(L.stream.size() * sizeof(uint32_t));
     a.X = static_cast<const uint16_t *>(X_dev);
     a.Y = Y_dev;
     a.ldx = ldx;
     a.ldy = ldy;
     a.M = p->M;
     a.K = p->K;
+    a.bh = p->bh;
     a.N = N;
     a.nrg = L.nrg;
     a.nch = L.nch;
@@ -764,15 +924,17 @@ ubp_status ubp_spmm_plan(const ubp_packed *p, const void *X_dev, int64_t ldx, in
     a.err = p->d_error;
     a.ctile0 = 0;
     a.n_coltiles = 0;
-    a.n_wgrows = (L.nrg + (waves - 1) - 1) / (waves - 1);
+    a.n_wgrows = wg_rows;
+    a.n_producers = NP;
+    a.resident = resident ? 1 : 0;
     const size_t ysz = (y_dtype == UBP_F32) ? 4 : 2;
     a.vec_ok = (ldx % 8 == 0) && (reinterpret_cast<uintptr_t>(X_dev) % 16 == 0) && ((ldy * ysz) % 16 == 0) &&
                (reinterpret_cast<uintptr_t>(Y_dev) % 16 == 0);
     if (p->dtype == UBP_BF16)
-        return y_dtype == UBP_F32 ? launch_stripe<true, float>(a, G, CT, waves, st)
-                                  : launch_stripe<true, __bf16>(a, G, CT, waves, st);
-    return y_dtype == UBP_F32 ? launch_stripe<false, float>(a, G, CT, waves, st)
-                              : launch_stripe<false, _Float16>(a, G, CT, waves, st);
+        return y_dtype == UBP_F32 ? launch_stripe<true, float>(a, G, CT, native, waves, st)
+                                  : launch_stripe<true, __bf16>(a, G, CT, native, waves, st);
+    return y_dtype == UBP_F32 ? launch_stripe<false, float>(a, G, CT, native, waves, st)
+                              : launch_stripe<false, _Float16>(a, G, CT, native, waves, st);
 }
 
 ubp_status ubp_packed_device_error(const ubp_packed *p, uint32_t *flags) {

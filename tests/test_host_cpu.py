@@ -159,3 +159,134 @@ def test_spmm_argument_errors_need_no_gpu():
     assert L.ubp_packed_info(h, 99) == -1 and L.ubp_packed_info(None, 0) == -1
     L.ubp_packed_free(None)
     p.free()
+
+
+# ---------------------------------------------------------------- private MFMA layouts
+def _ring_swizzle(CT, r):
+    return ((r >> 2) & 1) if CT == 2 else ((r >> 1) & 3) if CT == 4 else (r & 7)
+
+
+def _decode_layout(packed, G, CT, native, M, K, bh):
+    """Replays what the MFMA kernel does with a layout's step records, on the host and for the
+    weights only: which X row every gathered entry is (ring address -> row, through the
+    chunks the control words say are held) and which output rows every operand value feeds.
+    Returns the dense matrix the records stand for (16-bit patterns) and the MFMA count."""
+    rg_ptr, rg_order, stream = packed.layout(G, CT, native)
+    nrg = len(rg_order)
+    assert sorted(rg_order.tolist()) == list(range(nrg))
+    FG = 1 if native == 2 else G
+    rec_dw = 128 + 256 * FG
+    PITCH, RR = 32 * CT, 131072 // (32 * CT)
+    R = RR // 64
+    nch = -(-K // 64)
+    assert len(stream) == (rg_ptr[-1] + 4) * rec_dw          # four spare records at the end
+    lanes = np.arange(64)
+    g, t = lanes // 16, lanes % 16
+    e_in, sub = t // 4, (t % 4) * 8
+    idx_lo, idx_hi = 4 * g + e_in, 16 + 4 * g + e_in         # entry of the lane's two reads
+    Wd = np.zeros((nrg * 16 * G, K), dtype=np.uint16)
+    mfma = 0
+    for rg in range(nrg):
+        assert (rg_ptr[rg + 1] - rg_ptr[rg]) % 4 == 0
+        prev_rel = 0
+        for s in range(rg_ptr[rg], rg_ptr[rg + 1]):
+            rec = stream[s * rec_dw:(s + 1) * rec_dw]
+            d0, d1 = rec[0:128:2], rec[1:128:2]
+            mask = int(d0[0] >> 28)
+            assert np.all(d0 >> 28 == mask)
+            if native == 2:
+                ctl = int(sum(((int(d1[l]) >> 31) & 1) << l for l in range(32)))
+                assert np.all(d1[32:] >> 31 == 0)
+            else:
+                ctl = int(d1[0])
+                assert np.all(d1 == ctl)
+            need, rel = ctl & 0xffff, ctl >> 16
+            assert prev_rel <= rel <= nch                    # chunks are handed back in order
+            prev_rel = rel
+            if mask == 0:
+                assert not rec[128:].any()                   # an empty step carries no weights
+                continue
+            assert rel <= need < nch and need - rel <= R - 2  # held chunks leave two ring slots free
+            mfma += bin(mask).count("1")
+            ks = np.zeros((2, 64), dtype=np.int64)
+            for h, addr in enumerate(((d0 & 0x3fff).astype(np.int64) << 3, ((d0 >> 14) & 0x3fff).astype(np.int64) << 3)):
+                r = addr // PITCH
+                assert np.all(r < min(RR, nch * 64))
+                sw = np.array([_ring_swizzle(CT, int(x)) for x in r])
+                assert np.array_equal(addr % PITCH, (sw << 5) + sub)      # unit 0 of the row, swizzled, lane's 8 bytes
+                k = r + RR * ((rel * 64 - r + RR - 1) // RR)              # first row >= rel*64 congruent to r
+                assert np.all(k >= rel * 64) and np.all(k < (need + 1) * 64) and np.all(k < K)
+                ks[h] = k
+            # the four lanes of a quad read the same row; entry -> row
+            krow = np.zeros(32, dtype=np.int64)
+            krow[idx_lo], krow[idx_hi] = ks[0], ks[1]
+            assert np.array_equal(krow[idx_lo], ks[0]) and np.array_equal(krow[idx_hi], ks[1])
+            frag = rec[128:].view(np.uint16).reshape(FG, 64, 8)
+            ent = np.concatenate([(4 * g)[:, None] + np.arange(4), (16 + 4 * g)[:, None] + np.arange(4)], axis=1)  # [64, 8]
+            for j in range(G):
+                if not (mask >> j) & 1:
+                    if native != 2:
+                        assert not frag[j].any()
+                    continue
+                vals = frag[0 if native == 2 else j].copy()
+                if native == 2:
+                    t_lo = (d1 & 0x7f).astype(np.int64) - 64
+                    t_hi = ((d1 >> 8) & 0x7f).astype(np.int64) - 64
+                    lo_ok = (t_lo + 16 * j >= 0) & (t_lo + 16 * j < bh)
+                    hi_ok = (t_hi + 16 * j >= 0) & (t_hi + 16 * j < bh)
+                    vals[~lo_ok, :4] = 0
+                    vals[~hi_ok, 4:] = 0
+                rows = (rg * G + j) * 16 + t                                  # [64]
+                rr = np.repeat(rows[:, None], 8, axis=1)
+                kk = krow[ent]
+                nz = vals != 0
+                assert not Wd[rr[nz], kk[nz]].any()            # no weight is delivered twice
+                Wd[rr[nz], kk[nz]] = vals[nz]
+    assert not Wd[M:].any()
+    return Wd[:M], mfma
+
+
+LAYOUT_SHAPES = [(64, 64, 4, 4, 0.5), (100, 300, 8, 8, 0.2), (130, 600, 16, 16, 0.15), (33, 40, 5, 3, 0.3),
+                 (40, 2100, 4, 4, 0.02), (96, 2304, 4, 8, 0.1), (257, 31, 1, 1, 0.3), (90, 64, 20, 3, 0.25),
+                 (70, 4200, 16, 32, 0.08)]
+
+
+@pytest.mark.parametrize("shape", LAYOUT_SHAPES, ids=lambda s: "x".join(map(str, s)))
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+def test_private_layouts_decode_to_the_dense_matrix(shape, dtype):
+    M, K, bh, bw, d = shape
+    blocks = select_blocks(M, K, bh, bw, d, 77 + M, "uniform", 1.1)
+    W = make_weights(M, K, 5, dtype)
+    dense_bits = W.view(np.uint16).copy()
+    keep = oracle.densify(np.ones((M, K)), bh, bw, blocks) != 0
+    dense_bits[~keep] = 0
+    p = ubp.pack(W, dtype, bh, bw, blocks, device=ubp.HOST_ONLY)
+    eligible = bh <= 16 and bw in (4, 8, 16, 32)
+    for G in (1, 2, 4):
+        for CT in (2, 4, 8):
+            Wd, mfma = _decode_layout(p, G, CT, 1, M, K, bh)
+            assert np.array_equal(Wd, dense_bits), (G, CT)
+            assert mfma == p.info(100 + ubp.layout_slot(G, CT))
+            if eligible and G > 1:
+                Wn, mfma_n = _decode_layout(p, G, CT, 2, M, K, bh)
+                assert np.array_equal(Wn, dense_bits), ("native", G, CT)
+                assert mfma_n == p.info(300 + ubp.layout_slot(G, CT))
+            else:
+                with pytest.raises(ubp.UBPError):
+                    p.layout(G, CT, 2)
+    p.free()
+
+
+@pytest.mark.parametrize("cfg", [c for c in CONFIGS if c.dtype != "f32"], ids=lambda c: c.name)
+def test_benchmark_layer_layouts_decode_to_the_dense_matrix(cfg):
+    """The layouts the benchmark layers actually run with (and the block-native alternative)."""
+    from synthetic import make_layer
+    blocks, W, _ = make_layer(cfg, N=16)
+    dense_bits = W.view(np.uint16).copy()
+    dense_bits[oracle.densify(np.ones((cfg.M, cfg.K)), cfg.bh, cfg.bw, blocks) == 0] = 0
+    p = ubp.pack(W, cfg.dtype, cfg.bh, cfg.bw, blocks, device=ubp.HOST_ONLY)
+    G = 4 if cfg.bh >= 16 else 2 if cfg.bh >= 8 else 1
+    for g, ct, native in [(G, 8, 1), (G, 2, 1), (max(G, 2), 8, 2)]:
+        Wd, _ = _decode_layout(p, g, ct, native, cfg.M, cfg.K, cfg.bh)
+        assert np.array_equal(Wd, dense_bits), (g, ct, native)
+    p.free()

@@ -71,8 +71,33 @@ def test_stripe_kernel_small(shape, dtype):
         for y_dtype in (dtype, "f32"):
             Y = run_spmm(W, dtype, bh, bw, blocks, X, y_dtype, _plan(kernel=2, sub_stripes=G, col_tiles=CT))
             check(Y, Yref, Yabs, dtype, y_dtype)
-    for G, CT, waves in [(1, 4, 2), (2, 2, 5), (4, 8, 8), (2, 4, 16), (1, 2, 3)]:
+    for G, CT, waves in [(1, 4, 2), (2, 2, 5), (4, 8, 4), (4, 4, 8), (2, 4, 16), (1, 2, 3)]:
         Y = run_spmm(W, dtype, bh, bw, blocks, X, dtype, _plan(kernel=2, sub_stripes=G, col_tiles=CT, waves=waves))
+        check(Y, Yref, Yabs, dtype)
+    # several wavefronts staging X (each takes every n-th kilobyte of a chunk), and several
+    # workgroups sharing a column tile whose consumers walk more than one row group each
+    for G, CT, waves, producers, wg_rows in [(1, 2, 6, 4, 0), (1, 4, 3, 2, 0), (2, 8, 8, 4, 0), (4, 4, 5, 2, 0),
+                                             (2, 2, 0, 2, 0), (1, 8, 0, 4, 0), (1, 2, 2, 1, 1), (1, 4, 3, 1, 2),
+                                             (2, 2, 4, 2, 1), (1, 2, 5, 1, 3)]:
+        plan = _plan(kernel=2, sub_stripes=G, col_tiles=CT, waves=waves, producers=producers, wg_rows=wg_rows)
+        if wg_rows and -(-K // 64) > 64 // CT:
+            continue  # the staged tile does not hold all of K: the number of workgroup rows is not free
+        Y = run_spmm(W, dtype, bh, bw, blocks, X, dtype, plan)
+        check(Y, Yref, Yabs, dtype)
+    # block-native weight layout: whole blocks per step, one operand shared by the stripes
+    eligible = bh <= 16 and bw in (4, 8, 16, 32)
+    for G, CT in itertools.product((2, 4), (2, 4, 8)):
+        plan = _plan(kernel=2, sub_stripes=G, col_tiles=CT, native=2)
+        if not eligible:
+            with pytest.raises(ubp.UBPError):
+                run_spmm(W, dtype, bh, bw, blocks, X, dtype, plan)
+            continue
+        for y_dtype in (dtype, "f32"):
+            Y = run_spmm(W, dtype, bh, bw, blocks, X, y_dtype, plan)
+            check(Y, Yref, Yabs, dtype, y_dtype)
+    if eligible:
+        Y = run_spmm(W, dtype, bh, bw, blocks, X, dtype,
+                     _plan(kernel=2, sub_stripes=2, col_tiles=4, native=2, producers=2, waves=5))
         check(Y, Yref, Yabs, dtype)
 
 
@@ -225,3 +250,7 @@ def test_layer_full_size_sampled_rows(name):
     for G, CT in [(1, 8), (2, 8), (4, 4), (2, 2)]:
         Yp = run_spmm(W, cfg.dtype, cfg.bh, cfg.bw, blocks, X, "f32", _plan(kernel=2, sub_stripes=G, col_tiles=CT))
         assert np.abs(Yv - Yp).max() <= 1e-4 * np.abs(Yref).max(), (G, CT)
+    for G, CT, NP in [(4, 8, 2), (2, 4, 1), (4, 2, 4)]:
+        Yp = run_spmm(W, cfg.dtype, cfg.bh, cfg.bw, blocks, X, "f32",
+                      _plan(kernel=2, sub_stripes=G, col_tiles=CT, native=2, producers=NP))
+        assert np.abs(Yv - Yp).max() <= 1e-4 * np.abs(Yref).max(), ("native", G, CT)
