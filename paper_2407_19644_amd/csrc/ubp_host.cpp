@@ -428,6 +428,25 @@ static void build_one(ubp_packed *p, StripeLayout &L, int G, int CT, bool native
                 cmax = hi;
                 n += unit;
             }
+            if (!native && n > 8) {
+                // Order inside the step is free.  One transposed LDS read serves 16 entries, 8 per
+                // half wavefront, and those 8 rows hit distinct banks when their ring rows differ
+                // modulo 8 (the ring's swizzle): deal the entries, sorted by that residue, round-robin
+                // over the step's four groups of 8, so equal residues land in different groups.
+                std::stable_sort(entries.begin() + (std::ptrdiff_t)pos, entries.begin() + (std::ptrdiff_t)(pos + n),
+                                 [](const Entry &a, const Entry &b) { return (a.k & 7) < (b.k & 7); });
+                std::vector<Entry> dealt(n);
+                const size_t groups = (n + 7) / 8;
+                size_t at[4] = {0, 8, 16, 24};
+                for (size_t e = 0; e < n; ++e) {
+                    size_t gsel = e % groups;
+                    // a group that is already full (the last one may be shorter) passes its turn on
+                    for (size_t tries = 0; tries < groups && at[gsel] >= std::min(n, 8 * (gsel + 1)); ++tries)
+                        gsel = (gsel + 1) % groups;
+                    dealt[at[gsel]++] = entries[pos + e];
+                }
+                std::copy(dealt.begin(), dealt.end(), entries.begin() + (std::ptrdiff_t)pos);
+            }
             real.push_back(Step{pos, n, cmin, cmax, 0});
             pos += n;
         }

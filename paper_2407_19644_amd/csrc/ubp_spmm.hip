@@ -527,6 +527,18 @@ __global__ __launch_bounds__(stripe_max_threads(G, CT, D, NATIVE)) void stripe_k
     const int g = lane >> 4, n = lane & 15;
     TY *Yt = static_cast<TY *>(a.Y);
     for (;;) {
+        // the row group this wavefront takes next (resident mode), looked up before the step loop:
+        // the last D refills of the current row group then fetch ITS first D records, so that no
+        // record latency is paid between two row groups
+        const int q_next = q + q_step;
+        const bool more = q_next < a.nrg;
+        int rg_n = rg, s_n = s_all, s_all_n = s_all;
+        if (more) {
+            rg_n = __builtin_amdgcn_readfirstlane(a.rg_order[q_next]);
+            s_n = __builtin_amdgcn_readfirstlane(a.rg_ptr[rg_n]);
+            s_all_n = __builtin_amdgcn_readfirstlane(a.rg_ptr[rg_n + 1]);
+        }
+        bool handed_on = false; // the next row group's first records have been requested
 #pragma unroll
         for (int j = 0; j < G; ++j)
 #pragma unroll
@@ -534,6 +546,10 @@ __global__ __launch_bounds__(stripe_max_threads(G, CT, D, NATIVE)) void stripe_k
         if (s < s_all) {
             if constexpr (PIPE) stage(0, 0, false);
             for (; s < s_all; s += D) {
+                if (more && s + D >= s_all) {
+                    rec_next = (uint32_t)s_n * (uint32_t)REC_BYTES;
+                    handed_on = s_n < s_all_n;
+                }
 #pragma unroll
                 for (int d = 0; d < D; ++d) {
                     // the next step's gather first (or, with one operand buffer, this step's own)
@@ -568,13 +584,12 @@ __global__ __launch_bounds__(stripe_max_threads(G, CT, D, NATIVE)) void stripe_k
         }
         // the next row group's first records are requested before this one's tiles are stored
         const int rg_done = rg;
-        q += q_step;
-        const bool more = q < a.nrg;
+        q = q_next;
         if (more) {
-            rg = __builtin_amdgcn_readfirstlane(a.rg_order[q]);
-            s = __builtin_amdgcn_readfirstlane(a.rg_ptr[rg]);
-            s_all = __builtin_amdgcn_readfirstlane(a.rg_ptr[rg + 1]);
-            start_stream();
+            rg = rg_n;
+            s = s_n;
+            s_all = s_all_n;
+            if (!handed_on) start_stream();
         } else {
             release_upto(a.nch); // the last step's reads were consumed by its MFMAs
         }
