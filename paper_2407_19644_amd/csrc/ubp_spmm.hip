@@ -484,7 +484,7 @@ __global__ __launch_bounds__(stripe_max_threads(G, CT, D, NATIVE)) void stripe_k
     constexpr bool PIPE = stripe_pipelined(G, CT, NATIVE);
     const uint32_t ring_base = __builtin_amdgcn_readfirstlane(lds_address(smem));
     short8v xf[PIPE ? 2 : 1][CT];
-    auto stage = [&](int d, int b, bool foreign) {
+    auto stage_control = [&](int d, bool foreign, uint32_t &a_lo, uint32_t &a_hi) {
         // (foreign: the slot after the row group's last step holds another row group's record;
         // its gather is issued all the same, to valid addresses, and never used, but its control
         // word must not be acted on)
@@ -499,12 +499,39 @@ __global__ __launch_bounds__(stripe_max_threads(G, CT, D, NATIVE)) void stripe_k
         // absolute LDS addresses: the ring starts at a multiple of 1 KB, so adding its base
         // commutes with the XOR that selects the column tile
         const uint32_t ix = info_x[d];
-        const uint32_t a_lo = ring_base + ((ix & 0x3fffu) << 3), a_hi = ring_base + (((ix >> 14) & 0x3fffu) << 3);
+        a_lo = ring_base + ((ix & 0x3fffu) << 3);
+        a_hi = ring_base + (((ix >> 14) & 0x3fffu) << 3);
+    };
+    auto stage = [&](int d, int b, bool foreign) {
+        uint32_t a_lo, a_hi;
+        stage_control(d, foreign, a_lo, a_hi);
 #pragma unroll
         for (int c = 0; c < CT; ++c) {
             const short4v p0 = lds_read_tr(a_lo ^ (uint32_t)(c << 5));
             const short4v p1 = lds_read_tr(a_hi ^ (uint32_t)(c << 5));
             xf[b][c] = __builtin_shufflevector(p0, p1, 0, 1, 2, 3, 4, 5, 6, 7);
+        }
+    };
+    // One stripe per wavefront: the step is straight-line code (an empty step multiplies a zero
+    // fragment), and the gather of the next step is interleaved tile by tile with the MFMAs of
+    // the current one.  A wavefront issues in order and an MFMA occupies the matrix pipe for 16
+    // cycles: the two reads and two address operations placed behind each MFMA are then free
+    // instead of queueing up after a burst of MFMAs.
+    constexpr bool FUSED = PIPE && !NATIVE && G == 1;
+    auto fused = [&](int d, int dn, bool foreign) {
+        uint32_t a_lo, a_hi;
+        stage_control(dn, foreign, a_lo, a_hi);
+        const int cb = d & 1, nb = cb ^ 1;
+        const short8v wv = __builtin_bit_cast(short8v, wf[d][0]);
+#pragma unroll
+        for (int c = 0; c < CT; ++c) {
+            const short4v p0 = lds_read_tr(a_lo ^ (uint32_t)(c << 5));
+            const short4v p1 = lds_read_tr(a_hi ^ (uint32_t)(c << 5));
+            xf[nb][c] = __builtin_shufflevector(p0, p1, 0, 1, 2, 3, 4, 5, 6, 7);
+            acc[0][c] = mfma16<BF16>(xf[cb][c], wv, acc[0][c]);
+            __builtin_amdgcn_sched_group_barrier(0x002, 2, 0); // two address operations
+            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0); // two LDS reads
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0); // one MFMA
         }
     };
 
@@ -552,6 +579,11 @@ __global__ __launch_bounds__(stripe_max_threads(G, CT, D, NATIVE)) void stripe_k
                 }
 #pragma unroll
                 for (int d = 0; d < D; ++d) {
+                    if constexpr (FUSED) {
+                        fused(d, (d + 1) % D, d + 1 == D && s + D >= s_all);
+                        issue(d);
+                        continue;
+                    }
                     // the next step's gather first (or, with one operand buffer, this step's own)
                     if constexpr (PIPE) stage((d + 1) % D, (d + 1) & 1, d + 1 == D && s + D >= s_all);
                     else stage(d, 0, false);
