@@ -576,7 +576,40 @@ static void build_one(ubp_packed *p, StripeLayout &L, int G, int CT, bool native
     }
 }
 
+// Operand tiles for the small-K kernel.  Element e of lane (n = lane mod 16, g = lane / 16) of
+// tile (stripe, kt) is W[16*stripe + n][32*kt + i] with i = 4g + e for e < 4 and 16 + 4g + (e - 4)
+// otherwise: the order in which two transposed LDS reads deliver 32 consecutive rows of X.
+static void build_tiles(ubp_packed *p) {
+    TileLayout &T = p->tiles;
+    T.kt_pad = 0;
+    if (p->K > kTileMaxK) return;
+    const int M = p->M, K = p->K, bh = p->bh, bw = p->bw;
+    const int kt = (K + kStep - 1) / kStep;
+    T.kt_pad = std::max(2, ((kt + 1) / 2) * 2);
+    T.nstripes = (M + kStripe - 1) / kStripe;
+    T.frags.assign((size_t)T.nstripes * T.kt_pad * 512, 0);
+    T.masks.assign((size_t)T.nstripes, 0u);
+    const uint16_t *vals = reinterpret_cast<const uint16_t *>(p->values.data());
+    const int32_t nstart = M - bh + 1;
+    for (int i = 0; i < nstart; ++i)
+        for (int32_t b = p->indptr[(size_t)i]; b < p->indptr[(size_t)i + 1]; ++b) {
+            const int32_t c = p->indices[(size_t)b];
+            for (int q = 0; q < bw; ++q) {
+                const int k = c + q, t = k / kStep, idx = k % kStep;
+                // position of entry idx inside a lane's 8 elements, and the lane group that holds it
+                const int g = (idx % 16) / 4, e = (idx % 4) + (idx >= 16 ? 4 : 0);
+                for (int rho = i; rho < i + bh; ++rho) {
+                    const int stripe = rho / kStripe, n = rho % kStripe;
+                    const uint16_t v = vals[((int64_t)b * bw + q) * bh + (rho % bh)]; // rotated storage
+                    T.frags[(((size_t)stripe * T.kt_pad + t) * 64 + (size_t)(16 * g + n)) * 8 + e] = v;
+                    T.masks[(size_t)stripe] |= 1u << t;
+                }
+            }
+        }
+}
+
 void build_stripe_layouts(ubp_packed *p) {
+    build_tiles(p);
     if ((p->K + kSlotRows - 1) / kSlotRows > 0xffff) return; // chunk indices are 16-bit in the records
     for (int s = 0; s < kNumLayouts; ++s) build_one(p, p->sg[s], slot_G(s), slot_CT(s), false);
     // block-native layouts: a block must fit one 16-row operand (bh <= 16), whole blocks must tile

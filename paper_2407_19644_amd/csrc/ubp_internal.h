@@ -83,6 +83,22 @@ struct StripeLayout {
     int64_t total_mfma = 0; // MFMA issues per 16-column tile (steps x stripes with weights)
 };
 
+// Host image of the small-K kernel's layout: W as 16-row x 32-column operand tiles in MFMA
+// operand order, zeros where nothing is kept, for every (stripe, 32-column tile) pair, plus one
+// bit per pair that says whether the tile holds any kept weight (tiles without are skipped).
+// Built when K <= kTileMaxK; kt_pad = number of 32-column tiles rounded up to 2, 4, 6 or 8.
+constexpr int kTileMaxK = 256;
+struct TileLayout {
+    int kt_pad = 0;                  // 0: not built
+    int nstripes = 0;
+    std::vector<uint16_t> frags;     // [nstripes][kt_pad][64 lanes][8]
+    std::vector<uint32_t> masks;     // [nstripes]
+};
+struct TileLayoutDev {
+    uint16_t *frags = nullptr;
+    uint32_t *masks = nullptr;
+};
+
 struct StripeLayoutDev {
     int32_t *rg_ptr = nullptr;
     int32_t *rg_order = nullptr;
@@ -102,12 +118,14 @@ struct ubp_packed {
     // private layouts
     ubp::StripeLayout sg[ubp::kNumLayouts];
     ubp::StripeLayout sgn[ubp::kNumLayouts]; // block-native variants (G = 0 where not built)
+    ubp::TileLayout tiles;                   // small-K dense-tile layout (kt_pad = 0 where not built)
     // device side
     int32_t *d_indptr = nullptr;
     int32_t *d_indices = nullptr;
     float *d_values_f32 = nullptr; // rotated values widened to fp32 (exact)
     ubp::StripeLayoutDev d_sg[ubp::kNumLayouts];
     ubp::StripeLayoutDev d_sgn[ubp::kNumLayouts];
+    ubp::TileLayoutDev d_tiles;
     uint32_t *d_error = nullptr;   // set by a kernel whose bounded wait ran out
     int64_t device_bytes = 0;
 };

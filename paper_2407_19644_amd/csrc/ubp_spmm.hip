@@ -650,6 +650,175 @@ __global__ __launch_bounds__(stripe_max_threads(G, CT, D, NATIVE)) void stripe_k
     if (broken && lane == 0) atomicOr(a.err, 2u);
 }
 
+// ------------------------------------------------------------------ small-K tile kernel
+// For layers whose whole K dimension is a few 32-row tiles (K <= 256: pointwise convolutions
+// with few input channels).  There the gather machinery above costs more than it saves: with
+// 20-30 % of the weights kept in small blocks almost every 16 x 32 operand tile holds a kept
+// weight.  So W is used as zero-filled operand tiles, X needs no gather, and the kernel is a
+// short, fully unrolled, output-stationary loop:
+//  * Workgroup = NW wavefronts on NW neighbouring pixel tiles (16*CT pixels each) x one slice
+//    of up to 32/CT stripes, whose accumulators all stay in registers.
+//  * The slice's weight tiles (contiguous in memory) go global -> LDS once, all wavefronts
+//    taking turns at the 1 KB loads; every wavefront then reads each tile with one 16-byte
+//    LDS read per lane.
+//  * A wavefront requests its whole X tile at once (16 bytes per lane and load, full lines),
+//    then takes it 32 rows at a time through a private LDS scratch (written as loaded, read
+//    back transposed into operand order) and multiplies those 32 rows into every stripe of
+//    the slice: the MFMAs start when the first 32 rows have arrived and run while the rest is
+//    still on its way.  Columns past N and rows past K are staged as zeros.
+//  * Stores go through the same scratch: a lane holds 4 consecutive pixels of one row, so a
+//    direct store would write 16 separate 8- or 16-byte runs per instruction, which the
+//    memory pipeline takes one by one; read back with 16 bytes per lane and neighbouring
+//    lanes on neighbouring pieces of a row, the runs are 64 - 256 bytes.
+// Stripes of a partial last slice are computed (on the slice's last real tiles) but not stored.
+struct TileArgs {
+    const uint16_t *frags;   // [nstripes][KT][64][8]
+    const uint16_t *X;
+    void *Y;
+    int64_t ldx, ldy;
+    int M, K, N;
+    int nstripes, sps;       // stripes in all, stripes per workgroup slice (<= 32 / CT)
+    int n_blocks;            // pixel blocks (NW tiles each)
+};
+
+template <bool BF16, typename TY, int CT, int KT>
+__global__ __launch_bounds__(512) void tile_kernel(TileArgs a) {
+    constexpr int NTW = 16 * CT, PITCH = 32 * CT, PIECES = 2 * CT;
+    constexpr int SMAX = 32 / CT; // stripes whose accumulators fit the register file
+    extern __shared__ __attribute__((aligned(1024))) char smem[];
+    const int NW = (int)(blockDim.x >> 6);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    const int block = blockIdx.x % a.n_blocks, slice = blockIdx.x / a.n_blocks;
+    const int stripe0 = slice * a.sps;
+    const int ns = min(a.sps, a.nstripes - stripe0); // stripes of this slice
+    const int col0 = (block * NW + wave) * NTW;
+    const uint32_t lds0 = __builtin_amdgcn_readfirstlane(lds_address(smem));
+    const int w_bytes = a.sps * KT * 1024;            // weight area, then one scratch per wavefront
+    char *scratch = smem + w_bytes + wave * (32 * PITCH);
+
+    // ---- weight tiles of the slice: global -> LDS, 1 KB per instruction, wavefronts take turns
+    {
+        const uint16_t *src = a.frags + (int64_t)stripe0 * KT * 512;
+        const int n_kb = ns * KT;
+        for (int i = wave; i < n_kb; i += NW)
+            load16_to_lds(src + (int64_t)i * 512, (uint32_t)lane * 16u, lds0 + (uint32_t)i * 1024u);
+    }
+
+    // ---- every load of this wavefront's X tile is issued before the first one is used: the
+    // memory latency is paid once, not once per 32 rows
+    uint4 v[KT][CT];
+#pragma unroll
+    for (int kt = 0; kt < KT; ++kt) {
+#pragma unroll
+        for (int i = 0; i < CT; ++i) {
+            const int piece = lane + 64 * i;
+            const int r = piece / PIECES, q = piece % PIECES;
+            const int u = (q >> 1) ^ ring_swizzle(CT, r);  // logical 16-pixel unit stored at this position
+            const int col = col0 + u * 16 + (q & 1) * 8;
+            const int k = kt * 32 + r;
+            // always load (from a clamped, valid address) and zero afterwards: every wavefront then
+            // has exactly KT*CT loads behind its weight loads, which the wait before the barrier
+            // below counts on (N >= 8 here: a multiple of 8, and not 0)
+            const bool inside = k < a.K && col + 8 <= a.N;
+            const uint4 x = *reinterpret_cast<const uint4 *>(a.X + (int64_t)min(k, a.K - 1) * a.ldx + min(col, a.N - 8));
+            v[kt][i] = inside ? x : uint4{0u, 0u, 0u, 0u};
+        }
+    }
+
+    const int g = lane >> 4, n = lane & 15;
+    uint32_t a_lo, a_hi; // this lane's two transposed reads of a 32-row tile in the scratch
+    {
+        const int e_in = n >> 2, sub = (n & 3) * 8;
+        const int r_lo = 4 * g + e_in, r_hi = 16 + 4 * g + e_in;
+        const uint32_t s0 = lds_address(scratch);
+        a_lo = s0 + (uint32_t)(r_lo * PITCH + (ring_swizzle(CT, r_lo) << 5) + sub);
+        a_hi = s0 + (uint32_t)(r_hi * PITCH + (ring_swizzle(CT, r_hi) << 5) + sub);
+    }
+    typedef __attribute__((address_space(3))) const uint4v *lds_frag_ptr;
+    const uint32_t w_lane = lds0 + (uint32_t)lane * 16u;
+
+    float4v acc[SMAX][CT];
+#pragma unroll
+    for (int sl = 0; sl < SMAX; ++sl)
+#pragma unroll
+        for (int c = 0; c < CT; ++c) acc[sl][c] = float4v{0.f, 0.f, 0.f, 0.f};
+
+#pragma unroll
+    for (int kt = 0; kt < KT; ++kt) {
+        // 32 rows of X: registers -> scratch -> operand order.  (LDS executes a wavefront's
+        // operations in order: the reads of the previous 32 rows come before these writes, and
+        // the reads below after them.)
+#pragma unroll
+        for (int i = 0; i < CT; ++i) {
+            const int piece = lane + 64 * i;
+            *reinterpret_cast<uint4 *>(scratch + (piece / PIECES) * PITCH + (piece % PIECES) * 16) = v[kt][i];
+        }
+        asm volatile("" ::: "memory");
+        short8v xf[CT];
+#pragma unroll
+        for (int c = 0; c < CT; ++c) {
+            const short4v p0 = lds_read_tr(a_lo ^ (uint32_t)(c << 5));
+            const short4v p1 = lds_read_tr(a_hi ^ (uint32_t)(c << 5));
+            xf[c] = __builtin_shufflevector(p0, p1, 0, 1, 2, 3, 4, 5, 6, 7);
+        }
+        if (kt == 0) {
+            // Vector memory returns in order and the weight loads were issued before the X loads:
+            // once only the X loads of the later tiles are outstanding, this wavefront's share of
+            // the weight tiles has landed; after the barrier everybody's.
+            wait_vmcnt<(KT - 1) * CT>();
+            __syncthreads();
+        }
+#pragma unroll
+        for (int sl = 0; sl < SMAX; ++sl) {
+            const int sl_c = min(sl, ns - 1); // a partial slice recomputes its last stripe (never stored)
+            const uint4v w = *(lds_frag_ptr)(uintptr_t)(w_lane + (uint32_t)((sl_c * KT + kt) * 1024));
+            const short8v wv = __builtin_bit_cast(short8v, w);
+#pragma unroll
+            for (int c = 0; c < CT; ++c) acc[sl][c] = mfma16<BF16>(xf[c], wv, acc[sl][c]);
+        }
+    }
+
+    // ---- stores, through the scratch
+    constexpr int YS = (int)sizeof(TY);
+    constexpr int ROWB = NTW * YS;           // bytes of one output row of the tile
+    constexpr int NPC = ROWB / 16;           // 16-byte pieces per row (4, 8 or 16)
+    constexpr int SWZ = NPC < 8 ? NPC - 1 : 7;
+    constexpr int ROWS_PER = 64 / NPC;       // rows one store instruction covers
+    TY *Yt = static_cast<TY *>(a.Y);
+    const int r_in = lane / NPC, piece_out = lane % NPC;
+#pragma unroll
+    for (int sl = 0; sl < SMAX; ++sl) {
+        if (sl >= ns) continue; // (no break: the loop must unroll fully, accumulators are registers)
+        // lane (g, n): row n, pixels 16c + 4g .. + 3 -> byte (16c + 4g) * YS of the row
+#pragma unroll
+        for (int c = 0; c < CT; ++c) {
+            const int byte = (16 * c + 4 * g) * YS;
+            const int piece = (byte >> 4) ^ (n & SWZ);
+            char *dst = scratch + n * ROWB + piece * 16 + (byte & 15);
+            if constexpr (YS == 4) {
+                *reinterpret_cast<float4v *>(dst) = acc[sl][c];
+            } else {
+                typedef TY ty4 __attribute__((ext_vector_type(4)));
+                ty4 o;
+#pragma unroll
+                for (int t = 0; t < 4; ++t) o[t] = from_f32<TY>(acc[sl][c][t]);
+                *reinterpret_cast<ty4 *>(dst) = o;
+            }
+        }
+        asm volatile("" ::: "memory"); // LDS executes this wavefront's writes before its reads below
+#pragma unroll
+        for (int i = 0; i < 16 / ROWS_PER; ++i) {
+            const int r = i * ROWS_PER + r_in;
+            const uint4 o = *reinterpret_cast<const uint4 *>(scratch + r * ROWB + ((piece_out ^ (r & SWZ)) << 4));
+            const int row = (stripe0 + sl) * kStripe + r;
+            const int px = col0 + piece_out * (16 / YS);
+            if (row < a.M && px + 16 / YS <= a.N) *reinterpret_cast<uint4 *>(Yt + (int64_t)row * a.ldy + px) = o;
+        }
+        asm volatile("" ::: "memory");
+    }
+}
+
 // ------------------------------------------------------------------ launchers
 template <typename TX, typename TY, int VEC>
 ubp_status launch_wros_bh(const ubp_packed *p, const void *X, int64_t ldx, int N, void *Y, int64_t ldy, int rpr,
@@ -680,6 +849,34 @@ ubp_status launch_wros(const ubp_packed *p, const void *X, int64_t ldx, int N, v
                      (reinterpret_cast<uintptr_t>(Y) % (4 * sizeof(TY)) == 0) && N >= 2048;
     return vec ? launch_wros_bh<TX, TY, 4>(p, X, ldx, N, Y, ldy, rpr, st)
                : launch_wros_bh<TX, TY, 1>(p, X, ldx, N, Y, ldy, rpr, st);
+}
+
+template <bool BF16, typename TY, int CT, int KT>
+ubp_status launch_tile_inst(const TileArgs &a, int waves, int slices, hipStream_t st) {
+    const size_t lds = (size_t)a.sps * KT * 1024 + (size_t)waves * 32 * 32 * CT;
+    if (lds > 160 * 1024 || waves < 1 || waves > 8) return UBP_ERR_UNSUPPORTED;
+    static size_t attr_bytes = 0; // per instantiation; the limit is only ever raised
+    if (lds > attr_bytes) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&tile_kernel<BF16, TY, CT, KT>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
+            (void)hipGetLastError();
+            return UBP_ERR_DEVICE;
+        }
+        attr_bytes = lds;
+    }
+    hipLaunchKernelGGL((tile_kernel<BF16, TY, CT, KT>), dim3((unsigned)(a.n_blocks * slices)), dim3((unsigned)waves * 64), lds,
+                       st, a);
+    return hipGetLastError() == hipSuccess ? UBP_OK : UBP_ERR_DEVICE;
+}
+
+template <bool BF16, typename TY>
+ubp_status launch_tile(const TileArgs &a, int CT, int KT, int waves, int slices, hipStream_t st) {
+#define UBP_TILE_CASE(CC, KK) \
+    if (CT == CC && KT == KK) return launch_tile_inst<BF16, TY, CC, KK>(a, waves, slices, st);
+    UBP_TILE_CASE(2, 2) UBP_TILE_CASE(2, 4) UBP_TILE_CASE(2, 6) UBP_TILE_CASE(2, 8)
+    UBP_TILE_CASE(4, 2) UBP_TILE_CASE(4, 4) UBP_TILE_CASE(4, 6) UBP_TILE_CASE(4, 8)
+#undef UBP_TILE_CASE
+    return UBP_ERR_UNSUPPORTED;
 }
 
 template <bool BF16, typename TY, int G, int CT, bool FAST, bool NATIVE>
@@ -789,6 +986,10 @@ ubp_status upload(ubp_packed *p) {
             ok = ok && dev_copy(&D.rg_order, L.rg_order.data(), L.rg_order.size(), &p->device_bytes);
             ok = ok && dev_copy(&D.stream, L.stream.data(), L.stream.size(), &p->device_bytes);
         }
+        if (p->tiles.kt_pad) {
+            ok = ok && dev_copy(&p->d_tiles.frags, p->tiles.frags.data(), p->tiles.frags.size(), &p->device_bytes);
+            ok = ok && dev_copy(&p->d_tiles.masks, p->tiles.masks.data(), p->tiles.masks.size(), &p->device_bytes);
+        }
         for (int s = 0; s < kNumLayouts && ok; ++s) {
             const StripeLayout &L = p->sgn[s];
             if (L.G == 0) continue;
@@ -817,6 +1018,8 @@ void release_device(ubp_packed *p) {
     rel(p->d_indices);
     rel(p->d_values_f32);
     rel(p->d_error);
+    rel(p->d_tiles.frags);
+    rel(p->d_tiles.masks);
     for (int s = 0; s < kNumLayouts; ++s) {
         rel(p->d_sg[s].rg_ptr);
         rel(p->d_sg[s].rg_order);
@@ -849,9 +1052,52 @@ ubp_status ubp_spmm_plan(const ubp_packed *p, const void *X_dev, int64_t ldx, in
 
     int kernel = pl.kernel;
     if (kernel == 0) kernel = env_int("UBP_KERNEL", 0);
-    if (kernel == 0) kernel = (p->dtype == UBP_F32) ? 1 : 2;
-    if (kernel == 2 && p->dtype == UBP_F32) return UBP_ERR_UNSUPPORTED;
-    if (kernel != 1 && kernel != 2) return UBP_ERR_INVALID_ARG;
+    const size_t ysz = (y_dtype == UBP_F32) ? 4 : 2;
+    const bool vec_ok = (ldx % 8 == 0) && (reinterpret_cast<uintptr_t>(X_dev) % 16 == 0) && ((ldy * ysz) % 16 == 0) &&
+                        (reinterpret_cast<uintptr_t>(Y_dev) % 16 == 0);
+    // the small-K tile kernel needs 16-byte pieces of X rows that lie entirely inside or outside the matrix
+    const bool tile_ok = p->dtype != UBP_F32 && p->tiles.kt_pad != 0 && vec_ok && N % 8 == 0;
+    if (kernel == 0) kernel = (p->dtype == UBP_F32) ? 1 : tile_ok ? 3 : 2;
+    if ((kernel == 2 || kernel == 3) && p->dtype == UBP_F32) return UBP_ERR_UNSUPPORTED;
+    if (kernel < 1 || kernel > 3) return UBP_ERR_INVALID_ARG;
+    if (kernel == 3) {
+        if (!tile_ok) return UBP_ERR_UNSUPPORTED;
+        const int KT = p->tiles.kt_pad;
+        int CT = pl.col_tiles ? pl.col_tiles : env_int("UBP_CT", 0);
+        if (CT == 0) CT = 4;
+        if (CT != 2 && CT != 4) return UBP_ERR_UNSUPPORTED;
+        int waves = pl.waves ? pl.waves : env_int("UBP_WAVES", 0);
+        if (waves == 0) waves = 4;
+        if (waves < 1 || waves > 8) return UBP_ERR_UNSUPPORTED;
+        TileArgs a;
+        a.frags = p->d_tiles.frags;
+        a.X = static_cast<const uint16_t *>(X_dev);
+        a.Y = Y_dev;
+        a.ldx = ldx;
+        a.ldy = ldy;
+        a.M = p->M;
+        a.K = p->K;
+        a.N = N;
+        a.nstripes = p->tiles.nstripes;
+        a.n_blocks = (N + waves * 16 * CT - 1) / (waves * 16 * CT);
+        // Slices of stripes: a slice's accumulators must fit the registers (32 / CT stripes) and
+        // its weight tiles LDS beside the wavefronts' scratch; beyond that, as many workgroups as
+        // CUs where the pixel blocks alone are fewer (every slice re-reads the X block).
+        int slices = pl.wg_rows ? pl.wg_rows : env_int("UBP_WGROWS", 0);
+        if (slices < 0) return UBP_ERR_INVALID_ARG;
+        if (slices == 0) slices = std::max(1, (int)std::lround(256.0 / a.n_blocks));
+        slices = std::min(slices, a.nstripes);
+        const int max_sps = std::min(32 / CT, (int)((160 * 1024 - waves * 32 * 32 * CT) / (KT * 1024)));
+        if (max_sps < 1) return UBP_ERR_UNSUPPORTED;
+        slices = std::max(slices, (a.nstripes + max_sps - 1) / max_sps);
+        a.sps = (a.nstripes + slices - 1) / slices;
+        slices = (a.nstripes + a.sps - 1) / a.sps;
+        if (p->dtype == UBP_BF16)
+            return y_dtype == UBP_F32 ? launch_tile<true, float>(a, CT, KT, waves, slices, st)
+                                      : launch_tile<true, __bf16>(a, CT, KT, waves, slices, st);
+        return y_dtype == UBP_F32 ? launch_tile<false, float>(a, CT, KT, waves, slices, st)
+                                  : launch_tile<false, _Float16>(a, CT, KT, waves, slices, st);
+    }
 
     if (kernel == 1) {
         if (p->bh > 16) return UBP_ERR_UNSUPPORTED;
@@ -974,9 +1220,7 @@ ubp_status ubp_spmm_plan(const ubp_packed *p, const void *X_dev, int64_t ldx, in
     a.n_wgrows = wg_rows;
     a.n_producers = NP;
     a.resident = resident ? 1 : 0;
-    const size_t ysz = (y_dtype == UBP_F32) ? 4 : 2;
-    a.vec_ok = (ldx % 8 == 0) && (reinterpret_cast<uintptr_t>(X_dev) % 16 == 0) && ((ldy * ysz) % 16 == 0) &&
-               (reinterpret_cast<uintptr_t>(Y_dev) % 16 == 0);
+    a.vec_ok = vec_ok;
     if (p->dtype == UBP_BF16)
         return y_dtype == UBP_F32 ? launch_stripe<true, float>(a, G, CT, native, waves, st)
                                   : launch_stripe<true, __bf16>(a, G, CT, native, waves, st);

@@ -101,6 +101,44 @@ def test_stripe_kernel_small(shape, dtype):
         check(Y, Yref, Yabs, dtype)
 
 
+TILE_SHAPES = [(64, 64, 200, 4, 4, 0.5), (100, 200, 336, 8, 8, 0.2), (130, 256, 1000, 16, 16, 0.15), (33, 40, 136, 5, 3, 0.3),
+               (257, 31, 40, 1, 1, 0.3), (90, 64, 56, 20, 3, 0.25), (16, 16, 16, 16, 16, 1.0), (1040, 160, 520, 4, 4, 0.3),
+               (48, 250, 72, 2, 6, 0.05)]
+
+
+@pytest.mark.parametrize("shape", TILE_SHAPES, ids=lambda s: "x".join(map(str, s)))
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+def test_tile_kernel_small_k(shape, dtype):
+    """The small-K kernel (W as zero-filled operand tiles, X held in registers) in every tile
+    shape, workgroup size and slice count, including slices that end in a partial stripe and
+    pixel blocks that hang over the right edge."""
+    M, K, N, bh, bw, d = shape
+    blocks, W, X = _layer(M, K, N, bh, bw, d, dtype, seed=M + K + 3)
+    Yref, Yabs = _oracle(W, dtype, bh, bw, blocks, X)
+    for CT, waves, slices in [(4, 0, 0), (2, 0, 0), (4, 1, 1), (2, 8, 3), (4, 8, 2), (2, 3, 100), (4, 5, 7)]:
+        for y_dtype in (dtype, "f32"):
+            Y = run_spmm(W, dtype, bh, bw, blocks, X, y_dtype, _plan(kernel=3, col_tiles=CT, waves=waves, wg_rows=slices))
+            check(Y, Yref, Yabs, dtype, y_dtype)
+    # what ubp_spmm picks by itself for such a layer must be this kernel's result bit for bit
+    Ya = run_spmm(W, dtype, bh, bw, blocks, X, "f32")
+    Yt = run_spmm(W, dtype, bh, bw, blocks, X, "f32", _plan(kernel=3))
+    assert np.array_equal(Ya, Yt)
+
+
+def test_tile_kernel_refuses_what_it_cannot_do():
+    blocks, W, X = _layer(64, 300, 64, 4, 4, 0.3, "bf16", seed=5)       # K too large
+    with pytest.raises(ubp.UBPError):
+        run_spmm(W, "bf16", 4, 4, blocks, X, "bf16", _plan(kernel=3))
+    blocks, W, X = _layer(64, 64, 66, 4, 4, 0.3, "bf16", seed=6)        # N not a multiple of 8
+    with pytest.raises(ubp.UBPError):
+        run_spmm(W, "bf16", 4, 4, blocks, X, "bf16", _plan(kernel=3))
+    Yref, Yabs = _oracle(W, "bf16", 4, 4, blocks, X)
+    check(run_spmm(W, "bf16", 4, 4, blocks, X, "bf16"), Yref, Yabs, "bf16")  # falls back to the gather kernel
+    blocks, W, X = _layer(64, 64, 64, 4, 4, 0.3, "f32", seed=7)
+    with pytest.raises(ubp.UBPError):
+        run_spmm(W, "f32", 4, 4, blocks, X, "f32", _plan(kernel=3))
+
+
 @pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
 def test_unaligned_pitches_and_pointers(dtype):
     """Leading dimensions that are not multiples of the vector width take the element-wise
