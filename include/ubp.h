@@ -130,7 +130,7 @@ ubp_status ubp_spmm(const ubp_packed *p, const void *X_dev, int64_t ldx, int32_t
  *                rows of X a row group needs (f16 / bf16); 3 = MFMA kernel for K <= 256 that
  *                keeps X in registers and uses W as zero-filled 16 x 32 operand tiles (f16 /
  *                bf16, N a multiple of 8, 16-byte aligned rows of X and Y; col_tiles 2 or 4,
- *                waves 1..8 = neighbouring pixel tiles of a workgroup, wg_rows = slices of
+ *                waves 1, 2, 4 or 8 = neighbouring pixel tiles of a workgroup, wg_rows = slices of
  *                stripes).  0 picks 1 for fp32, 3 where it applies, else 2.
  *   sub_stripes: MFMA kernel, 16-row stripes per wavefront (1, 2 or 4).
  *   col_tiles  : MFMA kernel, 16-column tiles per wavefront (2, 4 or 8).

@@ -656,46 +656,56 @@ __global__ __launch_bounds__(stripe_max_threads(G, CT, D, NATIVE)) void stripe_k
 // 20-30 % of the weights kept in small blocks almost every 16 x 32 operand tile holds a kept
 // weight.  So W is used as zero-filled operand tiles, X needs no gather, and the kernel is a
 // short, fully unrolled, output-stationary loop:
-//  * Workgroup = NW wavefronts on NW neighbouring pixel tiles (16*CT pixels each) x one slice
-//    of up to 32/CT stripes, whose accumulators all stay in registers.
+//  * Workgroup = NW wavefronts on one block of NW*16*CT pixels (wavefront w owns pixel tile
+//    w) x one slice of up to SMAX stripes, whose accumulators all stay in registers.
 //  * The slice's weight tiles (contiguous in memory) go global -> LDS once, all wavefronts
 //    taking turns at the 1 KB loads; every wavefront then reads each tile with one 16-byte
 //    LDS read per lane.
-//  * A wavefront requests its whole X tile at once (16 bytes per lane and load, full lines),
-//    then takes it 32 rows at a time through a private LDS scratch (written as loaded, read
-//    back transposed into operand order) and multiplies those 32 rows into every stripe of
-//    the slice: the MFMAs start when the first 32 rows have arrived and run while the rest is
-//    still on its way.  Columns past N and rows past K are staged as zeros.
-//  * Stores go through the same scratch: a lane holds 4 consecutive pixels of one row, so a
-//    direct store would write 16 separate 8- or 16-byte runs per instruction, which the
-//    memory pipeline takes one by one; read back with 16 bytes per lane and neighbouring
-//    lanes on neighbouring pieces of a row, the runs are 64 - 256 bytes.
-// Stripes of a partial last slice are computed (on the slice's last real tiles) but not stored.
+//  * X is loaded by the workgroup together, block row by block row: an instruction's 64 lanes
+//    cover whole rows of the block (runs of NW*32*CT bytes) instead of 16 short runs of one
+//    wavefront's own columns - the memory pipeline takes a wavefront's runs one by one, and
+//    it is their number, not their bytes, that costs.  Every load is issued up front; the
+//    data then passes 32 rows at a time through one of two LDS staging tiles (one barrier
+//    per 32 rows), from which each wavefront reads its own columns transposed into operand
+//    order and multiplies them into every stripe of the slice: the MFMAs start when the
+//    first 32 rows have arrived and run while the rest is still on its way.
+//  * Stores leave the same way: accumulator tiles are written to LDS (the weight area, free
+//    by then) and the workgroup stores whole block rows, 16 bytes per lane.
+// Columns past N and rows past K are staged as zeros.  Stripes of a partial last slice are
+// computed (on the slice's last real tiles) but not stored.
 struct TileArgs {
     const uint16_t *frags;   // [nstripes][KT][64][8]
     const uint16_t *X;
     void *Y;
     int64_t ldx, ldy;
     int M, K, N;
-    int nstripes, sps;       // stripes in all, stripes per workgroup slice (<= 32 / CT)
+    int nstripes, sps;       // stripes in all, stripes per workgroup slice (<= SMAX)
     int n_blocks;            // pixel blocks (NW tiles each)
 };
 
-template <bool BF16, typename TY, int CT, int KT>
+// s_barrier with only the LDS counter drained: __syncthreads() would also wait for every
+// outstanding vector memory operation, i.e. for the X loads that are meant to stay in flight
+__device__ __forceinline__ void lds_barrier() {
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+template <bool BF16, typename TY, int CT, int KT, int SMAX>
 __global__ __launch_bounds__(512) void tile_kernel(TileArgs a) {
-    constexpr int NTW = 16 * CT, PITCH = 32 * CT, PIECES = 2 * CT;
-    constexpr int SMAX = 32 / CT; // stripes whose accumulators fit the register file
     extern __shared__ __attribute__((aligned(1024))) char smem[];
-    const int NW = (int)(blockDim.x >> 6);
+    const int NW = (int)(blockDim.x >> 6);                 // 1, 2, 4 or 8
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lane = threadIdx.x & 63;
     const int block = blockIdx.x % a.n_blocks, slice = blockIdx.x / a.n_blocks;
     const int stripe0 = slice * a.sps;
-    const int ns = min(a.sps, a.nstripes - stripe0); // stripes of this slice
-    const int col0 = (block * NW + wave) * NTW;
+    const int ns = min(a.sps, a.nstripes - stripe0);       // stripes of this slice
+    const int bcol0 = block * NW * 16 * CT;                // first pixel of the block
+    const int XRB = NW * 32 * CT;                          // bytes of one block row of X
+    const int U = NW * CT;                                 // 32-byte units per block row (power of two)
+    const int umask = min(U - 1, 15);
     const uint32_t lds0 = __builtin_amdgcn_readfirstlane(lds_address(smem));
-    const int w_bytes = a.sps * KT * 1024;            // weight area, then one scratch per wavefront
-    char *scratch = smem + w_bytes + wave * (32 * PITCH);
+    const int w_bytes = a.sps * KT * 1024;                 // weight area, then the two staging tiles
+    const int stage_bytes = 32 * XRB;
+    char *stage = smem + w_bytes;
 
     // ---- weight tiles of the slice: global -> LDS, 1 KB per instruction, wavefronts take turns
     {
@@ -705,21 +715,27 @@ __global__ __launch_bounds__(512) void tile_kernel(TileArgs a) {
             load16_to_lds(src + (int64_t)i * 512, (uint32_t)lane * 16u, lds0 + (uint32_t)i * 1024u);
     }
 
-    // ---- every load of this wavefront's X tile is issued before the first one is used: the
-    // memory latency is paid once, not once per 32 rows
+    // ---- X: instruction i (0 .. NW*CT-1) of a 32-row tile covers rows i*RPI .. of the block,
+    // lane -> (row, 16-byte piece of the block row); wavefront w issues instructions w*CT ..
+    const int LPR = 2 * U;                 // lanes (16-byte pieces) per block row
+    const int RPI = 64 / LPR;              // rows per instruction (LPR <= 64)
+    const int row_in = lane / LPR, piece = lane % LPR;
     uint4 v[KT][CT];
+    int st_off[CT];                        // where this lane's piece of instruction i goes in a staging tile
+#pragma unroll
+    for (int i = 0; i < CT; ++i) {
+        const int r = (wave * CT + i) * RPI + row_in; // row inside the 32-row tile
+        st_off[i] = r * XRB + (((piece >> 1) ^ (r & umask)) << 5) + ((piece & 1) << 4);
+    }
 #pragma unroll
     for (int kt = 0; kt < KT; ++kt) {
 #pragma unroll
         for (int i = 0; i < CT; ++i) {
-            const int piece = lane + 64 * i;
-            const int r = piece / PIECES, q = piece % PIECES;
-            const int u = (q >> 1) ^ ring_swizzle(CT, r);  // logical 16-pixel unit stored at this position
-            const int col = col0 + u * 16 + (q & 1) * 8;
-            const int k = kt * 32 + r;
+            const int k = kt * 32 + (wave * CT + i) * RPI + row_in;
+            const int col = bcol0 + piece * 8;
             // always load (from a clamped, valid address) and zero afterwards: every wavefront then
-            // has exactly KT*CT loads behind its weight loads, which the wait before the barrier
-            // below counts on (N >= 8 here: a multiple of 8, and not 0)
+            // has exactly KT*CT loads behind its weight loads, which the wait before the first
+            // barrier counts on (N >= 8 here: a multiple of 8, and not 0)
             const bool inside = k < a.K && col + 8 <= a.N;
             const uint4 x = *reinterpret_cast<const uint4 *>(a.X + (int64_t)min(k, a.K - 1) * a.ldx + min(col, a.N - 8));
             v[kt][i] = inside ? x : uint4{0u, 0u, 0u, 0u};
@@ -727,13 +743,12 @@ __global__ __launch_bounds__(512) void tile_kernel(TileArgs a) {
     }
 
     const int g = lane >> 4, n = lane & 15;
-    uint32_t a_lo, a_hi; // this lane's two transposed reads of a 32-row tile in the scratch
+    uint32_t a_lo, a_hi; // this lane's two transposed reads of its wavefront's columns in staging tile 0
     {
-        const int e_in = n >> 2, sub = (n & 3) * 8;
-        const int r_lo = 4 * g + e_in, r_hi = 16 + 4 * g + e_in;
-        const uint32_t s0 = lds_address(scratch);
-        a_lo = s0 + (uint32_t)(r_lo * PITCH + (ring_swizzle(CT, r_lo) << 5) + sub);
-        a_hi = s0 + (uint32_t)(r_hi * PITCH + (ring_swizzle(CT, r_hi) << 5) + sub);
+        const int r_lo = 4 * g + (n >> 2), r_hi = 16 + r_lo, sub = (n & 3) * 8;
+        const uint32_t s0 = lds_address(stage);
+        a_lo = s0 + (uint32_t)(r_lo * XRB + (((wave * CT) ^ (r_lo & umask)) << 5) + sub);
+        a_hi = s0 + (uint32_t)(r_hi * XRB + (((wave * CT) ^ (r_hi & umask)) << 5) + sub);
     }
     typedef __attribute__((address_space(3))) const uint4v *lds_frag_ptr;
     const uint32_t w_lane = lds0 + (uint32_t)lane * 16u;
@@ -746,28 +761,25 @@ __global__ __launch_bounds__(512) void tile_kernel(TileArgs a) {
 
 #pragma unroll
     for (int kt = 0; kt < KT; ++kt) {
-        // 32 rows of X: registers -> scratch -> operand order.  (LDS executes a wavefront's
-        // operations in order: the reads of the previous 32 rows come before these writes, and
-        // the reads below after them.)
+        // my pieces of these 32 rows -> staging tile kt mod 2.  (The tile was last read two
+        // barriers ago: nobody can still be reading it.)
+        char *st = stage + (kt & 1) * stage_bytes;
 #pragma unroll
-        for (int i = 0; i < CT; ++i) {
-            const int piece = lane + 64 * i;
-            *reinterpret_cast<uint4 *>(scratch + (piece / PIECES) * PITCH + (piece % PIECES) * 16) = v[kt][i];
-        }
-        asm volatile("" ::: "memory");
-        short8v xf[CT];
-#pragma unroll
-        for (int c = 0; c < CT; ++c) {
-            const short4v p0 = lds_read_tr(a_lo ^ (uint32_t)(c << 5));
-            const short4v p1 = lds_read_tr(a_hi ^ (uint32_t)(c << 5));
-            xf[c] = __builtin_shufflevector(p0, p1, 0, 1, 2, 3, 4, 5, 6, 7);
-        }
+        for (int i = 0; i < CT; ++i) *reinterpret_cast<uint4 *>(st + st_off[i]) = v[kt][i];
         if (kt == 0) {
             // Vector memory returns in order and the weight loads were issued before the X loads:
             // once only the X loads of the later tiles are outstanding, this wavefront's share of
             // the weight tiles has landed; after the barrier everybody's.
             wait_vmcnt<(KT - 1) * CT>();
-            __syncthreads();
+        }
+        lds_barrier();
+        short8v xf[CT];
+        const uint32_t off = (uint32_t)((kt & 1) * stage_bytes);
+#pragma unroll
+        for (int c = 0; c < CT; ++c) {
+            const short4v p0 = lds_read_tr((a_lo ^ (uint32_t)(c << 5)) + off);
+            const short4v p1 = lds_read_tr((a_hi ^ (uint32_t)(c << 5)) + off);
+            xf[c] = __builtin_shufflevector(p0, p1, 0, 1, 2, 3, 4, 5, 6, 7);
         }
 #pragma unroll
         for (int sl = 0; sl < SMAX; ++sl) {
@@ -779,23 +791,26 @@ __global__ __launch_bounds__(512) void tile_kernel(TileArgs a) {
         }
     }
 
-    // ---- stores, through the scratch
+    // ---- stores: tiles -> LDS (from its start: weights and staging tiles are dead) -> whole block rows
     constexpr int YS = (int)sizeof(TY);
-    constexpr int ROWB = NTW * YS;           // bytes of one output row of the tile
-    constexpr int NPC = ROWB / 16;           // 16-byte pieces per row (4, 8 or 16)
-    constexpr int SWZ = NPC < 8 ? NPC - 1 : 7;
-    constexpr int ROWS_PER = 64 / NPC;       // rows one store instruction covers
+    const int ORB = NW * 16 * CT * YS;       // bytes of one block row of Y
+    const int OPR = ORB / 16;                // 16-byte pieces per block row (a power of two, >= 4)
+    const int opr_shift = __builtin_ctz((unsigned)OPR);
+    const int osw = min(7, OPR - 1);         // pieces of a row are XOR-swizzled by the row number against bank conflicts
+    const int lds_bytes = w_bytes + 2 * stage_bytes;
+    const int chunk = max(1, min(ns, lds_bytes / (16 * ORB))); // stripes that fit LDS at a time
     TY *Yt = static_cast<TY *>(a.Y);
-    const int r_in = lane / NPC, piece_out = lane % NPC;
+    lds_barrier(); // everybody is done with the weights and the staging tiles
+    int in_chunk = 0, first = 0; // stripes written to LDS since the last flush, first of them
 #pragma unroll
     for (int sl = 0; sl < SMAX; ++sl) {
         if (sl >= ns) continue; // (no break: the loop must unroll fully, accumulators are registers)
-        // lane (g, n): row n, pixels 16c + 4g .. + 3 -> byte (16c + 4g) * YS of the row
+        // lane (g, n): row n of the stripe, pixels 16c + 4g .. + 3 of wavefront w's tile
 #pragma unroll
         for (int c = 0; c < CT; ++c) {
-            const int byte = (16 * c + 4 * g) * YS;
-            const int piece = (byte >> 4) ^ (n & SWZ);
-            char *dst = scratch + n * ROWB + piece * 16 + (byte & 15);
+            const int byte = ((wave * CT + c) * 16 + 4 * g) * YS;
+            const int pc = (byte >> 4) ^ (n & osw);
+            char *dst = smem + (in_chunk * 16 + n) * ORB + pc * 16 + (byte & 15);
             if constexpr (YS == 4) {
                 *reinterpret_cast<float4v *>(dst) = acc[sl][c];
             } else {
@@ -806,16 +821,21 @@ __global__ __launch_bounds__(512) void tile_kernel(TileArgs a) {
                 *reinterpret_cast<ty4 *>(dst) = o;
             }
         }
-        asm volatile("" ::: "memory"); // LDS executes this wavefront's writes before its reads below
-#pragma unroll
-        for (int i = 0; i < 16 / ROWS_PER; ++i) {
-            const int r = i * ROWS_PER + r_in;
-            const uint4 o = *reinterpret_cast<const uint4 *>(scratch + r * ROWB + ((piece_out ^ (r & SWZ)) << 4));
-            const int row = (stripe0 + sl) * kStripe + r;
-            const int px = col0 + piece_out * (16 / YS);
-            if (row < a.M && px + 16 / YS <= a.N) *reinterpret_cast<uint4 *>(Yt + (int64_t)row * a.ldy + px) = o;
+        ++in_chunk;
+        if (in_chunk == chunk || sl == ns - 1) {
+            lds_barrier(); // the chunk is complete
+            const int pieces = in_chunk * 16 * OPR;
+            for (int q = wave * 64 + lane; q < pieces; q += NW * 64) {
+                const int r = q >> opr_shift, pq = q & (OPR - 1);
+                const uint4 o = *reinterpret_cast<const uint4 *>(smem + r * ORB + ((pq ^ (r & osw)) << 4));
+                const int row = (stripe0 + first) * kStripe + r;
+                const int px = bcol0 + pq * (16 / YS);
+                if (row < a.M && px + 16 / YS <= a.N) *reinterpret_cast<uint4 *>(Yt + (int64_t)row * a.ldy + px) = o;
+            }
+            first = sl + 1;
+            in_chunk = 0;
+            if (sl != ns - 1) lds_barrier(); // the chunk has been read; the next one may overwrite it
         }
-        asm volatile("" ::: "memory");
     }
 }
 
@@ -851,28 +871,37 @@ ubp_status launch_wros(const ubp_packed *p, const void *X, int64_t ldx, int N, v
                : launch_wros_bh<TX, TY, 1>(p, X, ldx, N, Y, ldy, rpr, st);
 }
 
-template <bool BF16, typename TY, int CT, int KT>
+template <bool BF16, typename TY, int CT, int KT, int SMAX>
 ubp_status launch_tile_inst(const TileArgs &a, int waves, int slices, hipStream_t st) {
-    const size_t lds = (size_t)a.sps * KT * 1024 + (size_t)waves * 32 * 32 * CT;
-    if (lds > 160 * 1024 || waves < 1 || waves > 8) return UBP_ERR_UNSUPPORTED;
+    const size_t lds = (size_t)a.sps * KT * 1024 + (size_t)2 * 32 * waves * 32 * CT;
+    if (lds > 160 * 1024 || a.sps > SMAX) return UBP_ERR_UNSUPPORTED;
     static size_t attr_bytes = 0; // per instantiation; the limit is only ever raised
     if (lds > attr_bytes) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&tile_kernel<BF16, TY, CT, KT>),
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&tile_kernel<BF16, TY, CT, KT, SMAX>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
             (void)hipGetLastError();
             return UBP_ERR_DEVICE;
         }
         attr_bytes = lds;
     }
-    hipLaunchKernelGGL((tile_kernel<BF16, TY, CT, KT>), dim3((unsigned)(a.n_blocks * slices)), dim3((unsigned)waves * 64), lds,
-                       st, a);
+    hipLaunchKernelGGL((tile_kernel<BF16, TY, CT, KT, SMAX>), dim3((unsigned)(a.n_blocks * slices)), dim3((unsigned)waves * 64),
+                       lds, st, a);
     return hipGetLastError() == hipSuccess ? UBP_OK : UBP_ERR_DEVICE;
+}
+
+template <bool BF16, typename TY, int CT, int KT>
+ubp_status launch_tile_ck(const TileArgs &a, int waves, int slices, hipStream_t st) {
+    // the smallest accumulator set that holds the slice (unused stripes are computed all the same)
+    if (a.sps <= 4) return launch_tile_inst<BF16, TY, CT, KT, 4>(a, waves, slices, st);
+    if (a.sps <= 8) return launch_tile_inst<BF16, TY, CT, KT, 8>(a, waves, slices, st);
+    if constexpr (CT == 2) return launch_tile_inst<BF16, TY, CT, KT, 16>(a, waves, slices, st);
+    return UBP_ERR_UNSUPPORTED;
 }
 
 template <bool BF16, typename TY>
 ubp_status launch_tile(const TileArgs &a, int CT, int KT, int waves, int slices, hipStream_t st) {
 #define UBP_TILE_CASE(CC, KK) \
-    if (CT == CC && KT == KK) return launch_tile_inst<BF16, TY, CC, KK>(a, waves, slices, st);
+    if (CT == CC && KT == KK) return launch_tile_ck<BF16, TY, CC, KK>(a, waves, slices, st);
     UBP_TILE_CASE(2, 2) UBP_TILE_CASE(2, 4) UBP_TILE_CASE(2, 6) UBP_TILE_CASE(2, 8)
     UBP_TILE_CASE(4, 2) UBP_TILE_CASE(4, 4) UBP_TILE_CASE(4, 6) UBP_TILE_CASE(4, 8)
 #undef UBP_TILE_CASE
@@ -1064,11 +1093,11 @@ ubp_status ubp_spmm_plan(const ubp_packed *p, const void *X_dev, int64_t ldx, in
         if (!tile_ok) return UBP_ERR_UNSUPPORTED;
         const int KT = p->tiles.kt_pad;
         int CT = pl.col_tiles ? pl.col_tiles : env_int("UBP_CT", 0);
-        if (CT == 0) CT = 4;
+        if (CT == 0) CT = 2;
         if (CT != 2 && CT != 4) return UBP_ERR_UNSUPPORTED;
         int waves = pl.waves ? pl.waves : env_int("UBP_WAVES", 0);
-        if (waves == 0) waves = 4;
-        if (waves < 1 || waves > 8) return UBP_ERR_UNSUPPORTED;
+        if (waves == 0) waves = 8;
+        if (waves != 1 && waves != 2 && waves != 4 && waves != 8) return UBP_ERR_UNSUPPORTED;
         TileArgs a;
         a.frags = p->d_tiles.frags;
         a.X = static_cast<const uint16_t *>(X_dev);
@@ -1087,7 +1116,7 @@ ubp_status ubp_spmm_plan(const ubp_packed *p, const void *X_dev, int64_t ldx, in
         if (slices < 0) return UBP_ERR_INVALID_ARG;
         if (slices == 0) slices = std::max(1, (int)std::lround(256.0 / a.n_blocks));
         slices = std::min(slices, a.nstripes);
-        const int max_sps = std::min(32 / CT, (int)((160 * 1024 - waves * 32 * 32 * CT) / (KT * 1024)));
+        const int max_sps = std::min(32 / CT, (int)((160 * 1024 - 2 * 32 * waves * 32 * CT) / (KT * 1024)));
         if (max_sps < 1) return UBP_ERR_UNSUPPORTED;
         slices = std::max(slices, (a.nstripes + max_sps - 1) / max_sps);
         a.sps = (a.nstripes + slices - 1) / slices;
