@@ -217,7 +217,7 @@ def main():
                                         "y_dtype", "cache", "buffer_sets", "graph")},
         "roofline": {"bound": "hbm", "achieved": head["achieved_GBs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": head["hbm_frac"], "traffic": load_traffic(head["workload"], head["y_dtype"]),
-                     "kernel": "stripe_kernel" if cfg.dtype != "f32" and args.kernel != 1 else "wros_kernel",
+                     "kernel": ("wros_kernel" if cfg.dtype == "f32" or args.kernel == 1 else "tile_kernel" if (args.kernel == 3 or (args.kernel == 0 and cfg.K <= 256 and cfg.N % 8 == 0)) else "stripe_kernel"),
                      "kernel_us": head["kernel_us"], "algorithmic_bytes": head["algorithmic_bytes"],
                      "t_roof_us": head["t_roof_us"]},
     }
