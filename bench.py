@@ -144,6 +144,17 @@ def cpu_baseline(cfg, blocks, W, X, budget_s=15.0):
                       % (R, cfg.M, cfg.N, dt, 2.0 * R * cfg.K * cfg.N / dt / 1e9)}
 
 
+def kernel_name(cfg, pinned):
+    """The kernel ubp_spmm runs for this layer (same rule as the library's), or the pinned one."""
+    if cfg.dtype == "f32" or pinned == 1:
+        return "wros_kernel"
+    if pinned == 3:
+        return "tile_kernel"
+    if pinned == 4 or (pinned == 0 and cfg.K <= 256 and cfg.N % 8 == 0):
+        return "xstat_kernel"
+    return "stripe_kernel"
+
+
 def load_traffic(workload, y_dtype):
     """HBM bytes per launch from the committed rocprofv3 --pmc summaries, if present."""
     path = os.path.join(ROOT, "profiles", "traffic.json")
@@ -217,7 +228,7 @@ def main():
                                         "y_dtype", "cache", "buffer_sets", "graph")},
         "roofline": {"bound": "hbm", "achieved": head["achieved_GBs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": head["hbm_frac"], "traffic": load_traffic(head["workload"], head["y_dtype"]),
-                     "kernel": ("wros_kernel" if cfg.dtype == "f32" or args.kernel == 1 else "tile_kernel" if (args.kernel == 3 or (args.kernel == 0 and cfg.K <= 256 and cfg.N % 8 == 0)) else "stripe_kernel"),
+                     "kernel": kernel_name(cfg, args.kernel),
                      "kernel_us": head["kernel_us"], "algorithmic_bytes": head["algorithmic_bytes"],
                      "t_roof_us": head["t_roof_us"]},
     }

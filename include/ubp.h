@@ -127,11 +127,15 @@ ubp_status ubp_spmm(const ubp_packed *p, const void *X_dev, int64_t ldx, int32_t
  * "choose automatically"; an impossible combination returns UBP_ERR_UNSUPPORTED.
  *   kernel     : 1 = vector-ALU kernel that follows the WROS dataflow literally (any
  *                dtype, bh <= 16); 2 = MFMA kernel on aligned 16-row stripes that gathers the
- *                rows of X a row group needs (f16 / bf16); 3 = MFMA kernel for K <= 256 that
- *                keeps X in registers and uses W as zero-filled 16 x 32 operand tiles (f16 /
- *                bf16, N a multiple of 8, 16-byte aligned rows of X and Y; col_tiles 2 or 4,
- *                waves 1, 2, 4 or 8 = neighbouring pixel tiles of a workgroup, wg_rows = slices of
- *                stripes).  0 picks 1 for fp32, 3 where it applies, else 2.
+ *                rows of X a row group needs (f16 / bf16); 3 and 4 = MFMA kernels for K <= 256
+ *                that use W as zero-filled 16 x 32 operand tiles (f16 / bf16, N a multiple of
+ *                8, 16-byte aligned rows of X and Y; col_tiles 2 or 4; wg_rows = slices the
+ *                stripes are cut into, one workgroup per slice and pixel block).
+ *                3 keeps all stripes of a slice in accumulators and passes X through LDS 32 rows
+ *                at a time (waves 1, 2, 4 or 8 = neighbouring pixel tiles of a workgroup).
+ *                4 keeps the X of one pixel block in registers and streams the stripes past it,
+ *                16 finished rows at a time - the order of the paper's section 4.2 (waves 1..8
+ *                share a slice's stripes).  0 picks 1 for fp32, 4 where it applies, else 2.
  *   sub_stripes: MFMA kernel, 16-row stripes per wavefront (1, 2 or 4).
  *   col_tiles  : MFMA kernel, 16-column tiles per wavefront (2, 4 or 8).
  *   waves      : wavefronts per workgroup (MFMA kernel: producers + 1 .. 16).

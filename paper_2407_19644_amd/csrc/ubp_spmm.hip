@@ -839,6 +839,174 @@ __global__ __launch_bounds__(512) void tile_kernel(TileArgs a) {
     }
 }
 
+// ------------------------------------------------------------------ small-K kernel, X stationary in registers
+// The same operand tiles as tile_kernel, the loop nest the other way round - and closer to the
+// paper's dataflow (section 4.2), where output rows are finished one after the other and leave
+// for good.  K <= 256 means a wavefront can hold ALL of X for its 16*CT pixels as matrix
+// operands in registers (KT*CT fragments of 4 registers).  So:
+//  * Workgroup = NW wavefronts on ONE block of 16*CT pixels x one slice of stripes.  The block
+//    of X (K rows of 32*CT bytes) is loaded once by all wavefronts together, written to LDS
+//    already in the order in which the transposing reads want it (every such read then covers
+//    512 consecutive bytes: no bank conflicts by construction), and every wavefront reads all
+//    of it into registers.  That is the only barrier.
+//  * Then wavefront w streams the stripes w, w+NW, ... of the slice: KT loads fetch a stripe's
+//    weight tiles straight from memory in operand order (1 KB contiguous per instruction, each
+//    tile read by exactly one wavefront of the workgroup, so LDS would add nothing), the next
+//    stripe's loads are in flight while this stripe's KT*CT matrix instructions run, and the 16
+//    finished rows are stored at once.  Only CT accumulator tiles are alive at any time.
+// Pixels are dealt to the tiles so that a lane's results of two neighbouring tiles are 8
+// consecutive 16-bit pixels (one 16-byte store; the four lanes of a row then cover 64 bytes);
+// for a 32-bit Y a tile is 16 consecutive pixels.
+template <typename TY> struct PixelMap {
+    // first pixel (in the block) of the 4 consecutive pixels that form piece p of tile c
+    static constexpr bool kPairs = sizeof(TY) == 2;
+    __device__ static __forceinline__ int first(int c, int p) {
+        return kPairs ? 32 * (c >> 1) + 8 * p + 4 * (c & 1) : 16 * c + 4 * p;
+    }
+};
+
+template <bool BF16, typename TY, int CT, int KT>
+__global__ __launch_bounds__(512) void xstat_kernel(TileArgs a) {
+    extern __shared__ __attribute__((aligned(1024))) char smem[];
+    const int NW = (int)(blockDim.x >> 6);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    const int block = blockIdx.x % a.n_blocks, slice = blockIdx.x / a.n_blocks;
+    const int bcol0 = block * 16 * CT;
+
+    // ---- X block -> LDS.  LDS holds [kt][c][lo/hi half of the 32 rows][64 lanes] x 8 bytes: the
+    // 8 bytes lane (g', n') supplies to the transposing read of that half = 4 pixels (piece
+    // n' & 3 of tile c) of row 4 g' + (n' >> 2) of the half.
+    {
+        constexpr int LPR = 2 * CT;        // 16-byte pieces per block row
+        constexpr int RPI = 64 / LPR;      // rows per load instruction
+        constexpr int DEPTH = 4;           // loads in flight per lane
+        const int row_in = lane / LPR, q = lane % LPR;
+        const int col = bcol0 + 8 * q;
+        const bool col_in = col + 8 <= a.N;   // (N is a multiple of 8: a piece lies inside or outside)
+        const uint16_t *src = a.X + min(col, a.N - 8);
+        for (int r0 = wave * RPI + row_in; r0 < KT * 32; r0 += DEPTH * NW * RPI) {
+            uint4 v[DEPTH];
+#pragma unroll
+            for (int d = 0; d < DEPTH; ++d) {
+                const int k = r0 + d * NW * RPI;
+                const uint4 x = *reinterpret_cast<const uint4 *>(src + (int64_t)min(k, a.K - 1) * a.ldx);
+                v[d] = (col_in && k < a.K) ? x : uint4{0u, 0u, 0u, 0u};
+            }
+#pragma unroll
+            for (int d = 0; d < DEPTH; ++d) {
+                const int k = r0 + d * NW * RPI;
+                if (k < KT * 32) {
+                    const int kt = k >> 5, hi = (k >> 4) & 1, gg = (k >> 2) & 3, j = k & 3;
+#pragma unroll
+                    for (int h = 0; h < 2; ++h) {
+                        // the 4 pixels 8q + 4h .. of the block: tile c, piece pc
+                        int c, pc;
+                        if constexpr (PixelMap<TY>::kPairs) {
+                            c = 2 * (q >> 2) + h;
+                            pc = q & 3;
+                        } else {
+                            c = q >> 1;
+                            pc = 2 * (q & 1) + h;
+                        }
+                        char *dst = smem + (((kt * CT + c) * 2 + hi) << 9) + (gg << 7) + (j << 5) + (pc << 3);
+                        *reinterpret_cast<uint2 *>(dst) = h ? uint2{v[d].z, v[d].w} : uint2{v[d].x, v[d].y};
+                    }
+                }
+            }
+        }
+    }
+    __syncthreads();
+    short8v xf[KT][CT];
+    {
+        const uint32_t base = lds_address(smem) + (uint32_t)lane * 8u;
+#pragma unroll
+        for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+            for (int c = 0; c < CT; ++c) {
+                const short4v p0 = lds_read_tr(base + (uint32_t)(((kt * CT + c) * 2) << 9));
+                const short4v p1 = lds_read_tr(base + (uint32_t)(((kt * CT + c) * 2 + 1) << 9));
+                xf[kt][c] = __builtin_shufflevector(p0, p1, 0, 1, 2, 3, 4, 5, 6, 7);
+            }
+    }
+
+    // ---- stripes of the slice, NW apart
+    const int s_end = min(slice * a.sps + a.sps, a.nstripes);
+    int s = slice * a.sps + wave;
+    if (s >= s_end) return;
+    const int g = lane >> 4, n = lane & 15;
+    char *out_lds = smem + KT * CT * 1024 + wave * (256 * CT * (int)sizeof(TY)); // behind the X block
+    const uint4v *wbase = reinterpret_cast<const uint4v *>(a.frags) + lane;
+    TY *Yt = static_cast<TY *>(a.Y);
+    auto load_w = [&](uint4v(&w)[KT], int stripe) {
+        // (a stripe past the slice is clamped: loaded, never used)
+        const uint4v *src = wbase + (int64_t)min(stripe, a.nstripes - 1) * (KT * 64);
+#pragma unroll
+        for (int kt = 0; kt < KT; ++kt) w[kt] = src[kt * 64];
+    };
+    auto stripe_out = [&](const uint4v(&w)[KT], int stripe, bool valid) {
+        float4v acc[CT];
+#pragma unroll
+        for (int c = 0; c < CT; ++c) acc[c] = float4v{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int kt = 0; kt < KT; ++kt) {
+            const short8v wv = __builtin_bit_cast(short8v, w[kt]);
+#pragma unroll
+            for (int c = 0; c < CT; ++c) acc[c] = mfma16<BF16>(xf[kt][c], wv, acc[c]);
+        }
+        // The 16 x (16 CT) result leaves through this wavefront's own piece of LDS: in the
+        // accumulators a row is spread over 4 lanes (16 bytes each per store: 64-byte runs),
+        // after the detour an instruction writes whole rows of the block (RB bytes each).
+        // 16-byte pieces of a row are XOR-swizzled by the row number so that the 16 lanes LDS
+        // serves together hit 64 different banks on the way in and on the way out.
+        constexpr int RB = 16 * CT * (int)sizeof(TY);   // bytes per row: 64, 128 or 256
+        constexpr int PR = RB / 16;                     // pieces per row
+        constexpr int RP = 256 / RB;                    // rows per 256 bytes (one pass over the banks)
+        constexpr int NI = PR / 4;                      // pieces per lane = store instructions
+#pragma unroll
+        for (int jp = 0; jp < NI; ++jp) {
+            uint4v o;
+            if constexpr (PixelMap<TY>::kPairs) {
+                typedef TY ty8 __attribute__((ext_vector_type(8)));
+                ty8 t8;
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    t8[t] = from_f32<TY>(acc[2 * jp][t]);
+                    t8[4 + t] = from_f32<TY>(acc[2 * jp + 1][t]);
+                }
+                o = __builtin_bit_cast(uint4v, t8);
+            } else {
+                o = __builtin_bit_cast(uint4v, acc[jp]);
+            }
+            const int piece = (4 * jp + g) ^ ((n / RP) & (PR - 1));
+            *reinterpret_cast<uint4v *>(out_lds + n * RB + piece * 16) = o;
+        }
+        // (same wavefront writes and reads: LDS executes its instructions in order)
+#pragma unroll
+        for (int i = 0; i < NI; ++i) {
+            const int r = i * (64 / PR) + lane / PR, lp = lane % PR;
+            const uint4v o = *reinterpret_cast<const uint4v *>(out_lds + r * RB + ((lp ^ ((r / RP) & (PR - 1))) << 4));
+            const int row = stripe * kStripe + r;
+            const int px = bcol0 + lp * (16 / (int)sizeof(TY));
+            if (valid && row < a.M && px + 16 / (int)sizeof(TY) <= a.N)
+                *reinterpret_cast<uint4v *>(Yt + (int64_t)row * a.ldy + px) = o;
+        }
+    };
+    uint4v w0[KT], w1[KT];
+    load_w(w0, s);
+    // Two stripes per round, no exit in the middle: a stripe past the end is computed on the
+    // clamped tiles and not stored.  (The fences keep the compiler from sinking the next
+    // stripe's loads below this stripe's matrix instructions to save registers.)
+    for (; s < s_end; s += 2 * NW) {
+        load_w(w1, s + NW);
+        __builtin_amdgcn_sched_barrier(0);
+        stripe_out(w0, s, true);
+        load_w(w0, s + 2 * NW);
+        __builtin_amdgcn_sched_barrier(0);
+        stripe_out(w1, s + NW, s + NW < s_end);
+    }
+}
+
 // ------------------------------------------------------------------ launchers
 template <typename TX, typename TY, int VEC>
 ubp_status launch_wros_bh(const ubp_packed *p, const void *X, int64_t ldx, int N, void *Y, int64_t ldy, int rpr,
@@ -905,6 +1073,25 @@ ubp_status launch_tile(const TileArgs &a, int CT, int KT, int waves, int slices,
     UBP_TILE_CASE(2, 2) UBP_TILE_CASE(2, 4) UBP_TILE_CASE(2, 6) UBP_TILE_CASE(2, 8)
     UBP_TILE_CASE(4, 2) UBP_TILE_CASE(4, 4) UBP_TILE_CASE(4, 6) UBP_TILE_CASE(4, 8)
 #undef UBP_TILE_CASE
+    return UBP_ERR_UNSUPPORTED;
+}
+
+template <bool BF16, typename TY, int CT, int KT>
+ubp_status launch_xstat_inst(const TileArgs &a, int waves, int slices, hipStream_t st) {
+    // the X block, then 16 rows of output per wavefront: at most 32 + 32 KB, no attribute needed
+    const size_t lds = (size_t)KT * CT * 1024 + (size_t)waves * 256 * CT * sizeof(TY);
+    hipLaunchKernelGGL((xstat_kernel<BF16, TY, CT, KT>), dim3((unsigned)(a.n_blocks * slices)), dim3((unsigned)waves * 64),
+                       lds, st, a);
+    return hipGetLastError() == hipSuccess ? UBP_OK : UBP_ERR_DEVICE;
+}
+
+template <bool BF16, typename TY>
+ubp_status launch_xstat(const TileArgs &a, int CT, int KT, int waves, int slices, hipStream_t st) {
+#define UBP_XSTAT_CASE(CC, KK) \
+    if (CT == CC && KT == KK) return launch_xstat_inst<BF16, TY, CC, KK>(a, waves, slices, st);
+    UBP_XSTAT_CASE(2, 2) UBP_XSTAT_CASE(2, 4) UBP_XSTAT_CASE(2, 6) UBP_XSTAT_CASE(2, 8)
+    UBP_XSTAT_CASE(4, 2) UBP_XSTAT_CASE(4, 4) UBP_XSTAT_CASE(4, 6) UBP_XSTAT_CASE(4, 8)
+#undef UBP_XSTAT_CASE
     return UBP_ERR_UNSUPPORTED;
 }
 
@@ -1086,9 +1273,47 @@ ubp_status ubp_spmm_plan(const ubp_packed *p, const void *X_dev, int64_t ldx, in
                         (reinterpret_cast<uintptr_t>(Y_dev) % 16 == 0);
     // the small-K tile kernel needs 16-byte pieces of X rows that lie entirely inside or outside the matrix
     const bool tile_ok = p->dtype != UBP_F32 && p->tiles.kt_pad != 0 && vec_ok && N % 8 == 0;
-    if (kernel == 0) kernel = (p->dtype == UBP_F32) ? 1 : tile_ok ? 3 : 2;
-    if ((kernel == 2 || kernel == 3) && p->dtype == UBP_F32) return UBP_ERR_UNSUPPORTED;
-    if (kernel < 1 || kernel > 3) return UBP_ERR_INVALID_ARG;
+    if (kernel == 0) kernel = (p->dtype == UBP_F32) ? 1 : tile_ok ? 4 : 2;
+    if ((kernel == 2 || kernel == 3 || kernel == 4) && p->dtype == UBP_F32) return UBP_ERR_UNSUPPORTED;
+    if (kernel < 1 || kernel > 4) return UBP_ERR_INVALID_ARG;
+    if (kernel == 4) {
+        if (!tile_ok) return UBP_ERR_UNSUPPORTED;
+        const int KT = p->tiles.kt_pad;
+        int CT = pl.col_tiles ? pl.col_tiles : env_int("UBP_CT", 0);
+        // 64-pixel blocks halve the weight traffic per pixel; 32-pixel blocks where those would be few
+        if (CT == 0) CT = N >= 128 * 64 ? 4 : 2;
+        if (CT != 2 && CT != 4) return UBP_ERR_UNSUPPORTED;
+        TileArgs a;
+        a.frags = p->d_tiles.frags;
+        a.X = static_cast<const uint16_t *>(X_dev);
+        a.Y = Y_dev;
+        a.ldx = ldx;
+        a.ldy = ldy;
+        a.M = p->M;
+        a.K = p->K;
+        a.N = N;
+        a.nstripes = p->tiles.nstripes;
+        a.n_blocks = (N + 16 * CT - 1) / (16 * CT);
+        // Workgroups of 4 wavefronts, about one and a half per CU: two share a CU and the one's
+        // loading of X overlaps the other's streaming (measured better than one workgroup of 8).
+        // The stripes are cut into slices to get there - every slice loads the X block again, so
+        // only while a wavefront keeps at least 3 stripes.
+        int slices = pl.wg_rows ? pl.wg_rows : env_int("UBP_WGROWS", 0);
+        if (slices < 0) return UBP_ERR_INVALID_ARG;
+        if (slices == 0) slices = std::max(1, std::min((int)std::lround(384.0 / a.n_blocks), a.nstripes / 12));
+        slices = std::min(slices, a.nstripes);
+        a.sps = (a.nstripes + slices - 1) / slices;
+        slices = (a.nstripes + a.sps - 1) / a.sps;
+        int waves = pl.waves ? pl.waves : env_int("UBP_WAVES", 0);
+        if (waves == 0) waves = std::min(4, a.sps);
+        if (waves < 1 || waves > 8) return UBP_ERR_UNSUPPORTED;
+        if ((int64_t)a.n_blocks * slices > 0x7fffffff) return UBP_ERR_UNSUPPORTED;
+        if (p->dtype == UBP_BF16)
+            return y_dtype == UBP_F32 ? launch_xstat<true, float>(a, CT, KT, waves, slices, st)
+                                      : launch_xstat<true, __bf16>(a, CT, KT, waves, slices, st);
+        return y_dtype == UBP_F32 ? launch_xstat<false, float>(a, CT, KT, waves, slices, st)
+                                  : launch_xstat<false, _Float16>(a, CT, KT, waves, slices, st);
+    }
     if (kernel == 3) {
         if (!tile_ok) return UBP_ERR_UNSUPPORTED;
         const int KT = p->tiles.kt_pad;

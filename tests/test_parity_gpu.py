@@ -109,9 +109,9 @@ TILE_SHAPES = [(64, 64, 200, 4, 4, 0.5), (100, 200, 336, 8, 8, 0.2), (130, 256, 
 @pytest.mark.parametrize("shape", TILE_SHAPES, ids=lambda s: "x".join(map(str, s)))
 @pytest.mark.parametrize("dtype", ["f16", "bf16"])
 def test_tile_kernel_small_k(shape, dtype):
-    """The small-K kernel (W as zero-filled operand tiles, X held in registers) in every tile
-    shape, workgroup size and slice count, including slices that end in a partial stripe and
-    pixel blocks that hang over the right edge."""
+    """The output-stationary small-K kernel (W as zero-filled operand tiles in LDS, X staged
+    through LDS 32 rows at a time) in every tile shape, workgroup size and slice count,
+    including slices that end in a partial stripe and pixel blocks that hang over the right edge."""
     M, K, N, bh, bw, d = shape
     blocks, W, X = _layer(M, K, N, bh, bw, d, dtype, seed=M + K + 3)
     Yref, Yabs = _oracle(W, dtype, bh, bw, blocks, X)
@@ -119,24 +119,47 @@ def test_tile_kernel_small_k(shape, dtype):
         for y_dtype in (dtype, "f32"):
             Y = run_spmm(W, dtype, bh, bw, blocks, X, y_dtype, _plan(kernel=3, col_tiles=CT, waves=waves, wg_rows=slices))
             check(Y, Yref, Yabs, dtype, y_dtype)
+
+
+@pytest.mark.parametrize("shape", TILE_SHAPES, ids=lambda s: "x".join(map(str, s)))
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+def test_x_stationary_kernel_small_k(shape, dtype):
+    """The other small-K kernel (X of a pixel block held in registers as operands, stripes of
+    W streamed past it, 16 finished rows stored at a time) in both tile widths, every
+    workgroup size and several slice counts: more wavefronts than stripes, an odd number of
+    stripes per wavefront, a pixel block that hangs over the right edge, a last stripe that
+    hangs over the bottom."""
+    M, K, N, bh, bw, d = shape
+    blocks, W, X = _layer(M, K, N, bh, bw, d, dtype, seed=M + K + 4)
+    Yref, Yabs = _oracle(W, dtype, bh, bw, blocks, X)
+    for CT, waves, slices in [(4, 0, 0), (2, 0, 0), (4, 1, 1), (2, 8, 3), (4, 8, 1), (2, 3, 100), (4, 5, 2), (2, 1, 2),
+                              (4, 7, 1), (2, 2, 1)]:
+        for y_dtype in (dtype, "f32"):
+            Y = run_spmm(W, dtype, bh, bw, blocks, X, y_dtype, _plan(kernel=4, col_tiles=CT, waves=waves, wg_rows=slices))
+            check(Y, Yref, Yabs, dtype, y_dtype)
     # what ubp_spmm picks by itself for such a layer must be this kernel's result bit for bit
     Ya = run_spmm(W, dtype, bh, bw, blocks, X, "f32")
-    Yt = run_spmm(W, dtype, bh, bw, blocks, X, "f32", _plan(kernel=3))
+    Yt = run_spmm(W, dtype, bh, bw, blocks, X, "f32", _plan(kernel=4))
     assert np.array_equal(Ya, Yt)
 
 
-def test_tile_kernel_refuses_what_it_cannot_do():
+@pytest.mark.parametrize("kernel", [3, 4])
+def test_small_k_kernels_refuse_what_they_cannot_do(kernel):
     blocks, W, X = _layer(64, 300, 64, 4, 4, 0.3, "bf16", seed=5)       # K too large
     with pytest.raises(ubp.UBPError):
-        run_spmm(W, "bf16", 4, 4, blocks, X, "bf16", _plan(kernel=3))
+        run_spmm(W, "bf16", 4, 4, blocks, X, "bf16", _plan(kernel=kernel))
     blocks, W, X = _layer(64, 64, 66, 4, 4, 0.3, "bf16", seed=6)        # N not a multiple of 8
     with pytest.raises(ubp.UBPError):
-        run_spmm(W, "bf16", 4, 4, blocks, X, "bf16", _plan(kernel=3))
+        run_spmm(W, "bf16", 4, 4, blocks, X, "bf16", _plan(kernel=kernel))
     Yref, Yabs = _oracle(W, "bf16", 4, 4, blocks, X)
     check(run_spmm(W, "bf16", 4, 4, blocks, X, "bf16"), Yref, Yabs, "bf16")  # falls back to the gather kernel
     blocks, W, X = _layer(64, 64, 64, 4, 4, 0.3, "f32", seed=7)
     with pytest.raises(ubp.UBPError):
-        run_spmm(W, "f32", 4, 4, blocks, X, "f32", _plan(kernel=3))
+        run_spmm(W, "f32", 4, 4, blocks, X, "f32", _plan(kernel=kernel))
+    blocks, W, X = _layer(64, 64, 64, 4, 4, 0.3, "bf16", seed=8)
+    for bad in (dict(col_tiles=8), dict(waves=9), dict(col_tiles=3)):
+        with pytest.raises(ubp.UBPError):
+            run_spmm(W, "bf16", 4, 4, blocks, X, "bf16", _plan(kernel=kernel, **bad))
 
 
 @pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
