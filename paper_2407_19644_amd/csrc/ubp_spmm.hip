@@ -874,29 +874,52 @@ __global__ __launch_bounds__(512) void xstat_kernel(TileArgs a) {
     const int block = blockIdx.x % a.n_blocks, slice = blockIdx.x / a.n_blocks;
     const int bcol0 = block * 16 * CT;
 
+    // the first stripe's weight tiles are on their way while X is loaded
+    const int s_end = min(slice * a.sps + a.sps, a.nstripes);
+    int s = slice * a.sps + wave;
+    const uint4v *wbase = reinterpret_cast<const uint4v *>(a.frags) + lane;
+    auto load_w = [&](uint4v(&w)[KT], int stripe) {
+        // (a stripe past the slice is clamped: loaded, never used)
+        const uint4v *src = wbase + (int64_t)min(stripe, a.nstripes - 1) * (KT * 64);
+#pragma unroll
+        for (int kt = 0; kt < KT; ++kt) w[kt] = src[kt * 64];
+    };
+    uint4v w0[KT], w1[KT];
+    load_w(w0, s);
+
     // ---- X block -> LDS.  LDS holds [kt][c][lo/hi half of the 32 rows][64 lanes] x 8 bytes: the
     // 8 bytes lane (g', n') supplies to the transposing read of that half = 4 pixels (piece
     // n' & 3 of tile c) of row 4 g' + (n' >> 2) of the half.
     {
         constexpr int LPR = 2 * CT;        // 16-byte pieces per block row
         constexpr int RPI = 64 / LPR;      // rows per load instruction
-        constexpr int DEPTH = 4;           // loads in flight per lane
+        constexpr int DEPTH = 8;           // loads in flight per lane (all of them for 4 wavefronts, CT = 4, K = 256)
         const int row_in = lane / LPR, q = lane % LPR;
         const int col = bcol0 + 8 * q;
         const bool col_in = col + 8 <= a.N;   // (N is a multiple of 8: a piece lies inside or outside)
         const uint16_t *src = a.X + min(col, a.N - 8);
-        for (int r0 = wave * RPI + row_in; r0 < KT * 32; r0 += DEPTH * NW * RPI) {
+        // (u0: first row of this wavefront's instruction, wave-uniform; an instruction lies
+        // entirely inside or outside the KT * 32 rows, which are a multiple of RPI)
+        // (unrolled to the batch count of a single wavefront, not a loop: in front of a loop the
+        // compiler would first wait for the weight loads above)
+        constexpr int BATCHES = (KT * 32 + DEPTH * RPI - 1) / (DEPTH * RPI);
+#pragma unroll
+        for (int b = 0; b < BATCHES; ++b) {
+            const int u0 = wave * RPI + b * DEPTH * NW * RPI;
+            if (u0 >= KT * 32) break;
             uint4 v[DEPTH];
 #pragma unroll
             for (int d = 0; d < DEPTH; ++d) {
-                const int k = r0 + d * NW * RPI;
+                // (no branch around the load - the compiler would wait for each one at the join;
+                // rows past the end load row K - 1 again and are dropped below)
+                const int k = u0 + d * NW * RPI + row_in;
                 const uint4 x = *reinterpret_cast<const uint4 *>(src + (int64_t)min(k, a.K - 1) * a.ldx);
                 v[d] = (col_in && k < a.K) ? x : uint4{0u, 0u, 0u, 0u};
             }
 #pragma unroll
             for (int d = 0; d < DEPTH; ++d) {
-                const int k = r0 + d * NW * RPI;
-                if (k < KT * 32) {
+                const int k = u0 + d * NW * RPI + row_in;
+                if (u0 + d * NW * RPI < KT * 32) {
                     const int kt = k >> 5, hi = (k >> 4) & 1, gg = (k >> 2) & 3, j = k & 3;
 #pragma unroll
                     for (int h = 0; h < 2; ++h) {
@@ -931,19 +954,10 @@ __global__ __launch_bounds__(512) void xstat_kernel(TileArgs a) {
     }
 
     // ---- stripes of the slice, NW apart
-    const int s_end = min(slice * a.sps + a.sps, a.nstripes);
-    int s = slice * a.sps + wave;
     if (s >= s_end) return;
     const int g = lane >> 4, n = lane & 15;
     char *out_lds = smem + KT * CT * 1024 + wave * (256 * CT * (int)sizeof(TY)); // behind the X block
-    const uint4v *wbase = reinterpret_cast<const uint4v *>(a.frags) + lane;
     TY *Yt = static_cast<TY *>(a.Y);
-    auto load_w = [&](uint4v(&w)[KT], int stripe) {
-        // (a stripe past the slice is clamped: loaded, never used)
-        const uint4v *src = wbase + (int64_t)min(stripe, a.nstripes - 1) * (KT * 64);
-#pragma unroll
-        for (int kt = 0; kt < KT; ++kt) w[kt] = src[kt * 64];
-    };
     auto stripe_out = [&](const uint4v(&w)[KT], int stripe, bool valid) {
         float4v acc[CT];
 #pragma unroll
@@ -992,8 +1006,6 @@ __global__ __launch_bounds__(512) void xstat_kernel(TileArgs a) {
                 *reinterpret_cast<uint4v *>(Yt + (int64_t)row * a.ldy + px) = o;
         }
     };
-    uint4v w0[KT], w1[KT];
-    load_w(w0, s);
     // Two stripes per round, no exit in the middle: a stripe past the end is computed on the
     // clamped tiles and not stored.  (The fences keep the compiler from sinking the next
     // stripe's loads below this stripe's matrix instructions to save registers.)
