@@ -152,6 +152,9 @@ def kernel_name(cfg, pinned):
         return "tile_kernel"
     if pinned == 4 or (pinned == 0 and cfg.K <= 256 and cfg.N % 8 == 0):
         return "xstat_kernel"
+    tiles_mb = ((cfg.M + 15) // 16) * 8 * ((cfg.K + 255) // 256) / 1024.0   # zero-filled W as operand tiles
+    if pinned == 5 or (pinned == 0 and cfg.N % 8 == 0 and tiles_mb <= 8 and cfg.density >= 0.2):
+        return "xchunk_kernel"
     return "stripe_kernel"
 
 

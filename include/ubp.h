@@ -127,15 +127,20 @@ ubp_status ubp_spmm(const ubp_packed *p, const void *X_dev, int64_t ldx, int32_t
  * "choose automatically"; an impossible combination returns UBP_ERR_UNSUPPORTED.
  *   kernel     : 1 = vector-ALU kernel that follows the WROS dataflow literally (any
  *                dtype, bh <= 16); 2 = MFMA kernel on aligned 16-row stripes that gathers the
- *                rows of X a row group needs (f16 / bf16); 3 and 4 = MFMA kernels for K <= 256
- *                that use W as zero-filled 16 x 32 operand tiles (f16 / bf16, N a multiple of
- *                8, 16-byte aligned rows of X and Y; col_tiles 2 or 4; wg_rows = slices the
- *                stripes are cut into, one workgroup per slice and pixel block).
- *                3 keeps all stripes of a slice in accumulators and passes X through LDS 32 rows
- *                at a time (waves 1, 2, 4 or 8 = neighbouring pixel tiles of a workgroup).
- *                4 keeps the X of one pixel block in registers and streams the stripes past it,
- *                16 finished rows at a time - the order of the paper's section 4.2 (waves 1..8
- *                share a slice's stripes).  0 picks 1 for fp32, 4 where it applies, else 2.
+ *                rows of X a row group needs (f16 / bf16); 3, 4 and 5 = MFMA kernels that use W
+ *                as zero-filled 16 x 32 operand tiles (f16 / bf16, N a multiple of 8, 16-byte
+ *                aligned rows of X and Y; col_tiles 2 or 4; wg_rows = slices the stripes are
+ *                cut into, one workgroup per slice and pixel block).
+ *                3 (K <= 256) keeps all stripes of a slice in accumulators and passes X through
+ *                LDS 32 rows at a time (waves 1, 2, 4 or 8 = neighbouring pixel tiles).
+ *                4 (K <= 256) keeps the X of one pixel block in registers and streams the stripes
+ *                past it, 16 finished rows at a time - the order of the paper's section 4.2
+ *                (waves 1..8 share a slice's stripes).
+ *                5 (any K whose zero-filled W stays below 8 MB) cuts K into chunks of 128 rows
+ *                that pass through LDS and the registers while the accumulators of 16 stripes
+ *                stay (sub_stripes 2 or 4 = stripes per multiplying wavefront; waves fixed).
+ *                0 picks 1 for fp32; 4 for K <= 256; 5 for larger K when at least a fifth of W is
+ *                kept; else 2.
  *   sub_stripes: MFMA kernel, 16-row stripes per wavefront (1, 2 or 4).
  *   col_tiles  : MFMA kernel, 16-column tiles per wavefront (2, 4 or 8).
  *   waves      : wavefronts per workgroup (MFMA kernel: producers + 1 .. 16).
@@ -183,6 +188,11 @@ int64_t ubp_packed_info(const ubp_packed *p, int32_t what);
  *   rg_order : int32[row groups], row groups by decreasing work
  *   stream   : uint32[stream_words], the step records (format: comment of StripeLayout in
  *              csrc/ubp_internal.h)
+ * native = 3 views the dense operand tiles of kernels 3 to 5 instead (sub_stripes and col_tiles
+ * are ignored): row_groups = number of 16-row stripes, rg_ptr = rg_order = NULL, stream =
+ * [stripes][tiles per stripe][64 lanes][8] 16-bit weights as 32-bit words (tiles per stripe =
+ * stream_words / (256 * stripes)); lane 16 g + n of a tile holds row n of the stripe, columns
+ * 4 g .. 4 g + 3 and 16 + 4 g .. 16 + 4 g + 3 of the tile's 32.
  * Returns UBP_ERR_UNSUPPORTED when that layout was not built for this matrix (fp32, K too
  * large, block shape not eligible).  Any output pointer may be NULL.
  */

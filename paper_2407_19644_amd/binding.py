@@ -124,7 +124,8 @@ class Packed:
         return int(load_library().ubp_packed_info(self.handle, what))
 
     def layout(self, sub_stripes, col_tiles, native=1):
-        """ubp_packed_layout -> (rg_ptr int32[nrg + 1], rg_order int32[nrg], stream uint32[...]) as copies."""
+        """ubp_packed_layout -> (rg_ptr int32[nrg + 1], rg_order int32[nrg], stream uint32[...]) as copies;
+        native=3: the dense operand tiles as (None, None, uint16[stripes][tiles][64][8])."""
         nrg = ctypes.c_int32(0)
         words = ctypes.c_int64(0)
         a, b, c = ctypes.c_void_p(), ctypes.c_void_p(), ctypes.c_void_p()
@@ -138,6 +139,9 @@ class Packed:
                 return np.zeros(0, dtype=dt)
             buf = (ctypes.c_char * (n * np.dtype(dt).itemsize)).from_address(ptr.value)
             return np.frombuffer(buf, dtype=dt).copy()
+        if native == 3:   # dense operand tiles: (None, None, uint16[stripes][tiles][64][8])
+            t = copy(c, words.value, np.uint32).view(np.uint16)
+            return None, None, t.reshape(nrg.value, -1, 64, 8)
         return (copy(a, nrg.value + 1, np.int32), copy(b, nrg.value, np.int32), copy(c, words.value, np.uint32))
 
     def _view(self, fn, np_dtype):

@@ -280,7 +280,18 @@ int64_t ubp_packed_info(const ubp_packed *p, int32_t what) {
 ubp_status ubp_packed_layout(const ubp_packed *p, int32_t sub_stripes, int32_t col_tiles, int32_t native,
                              int32_t *row_groups, const int32_t **rg_ptr, const int32_t **rg_order,
                              const uint32_t **stream, int64_t *stream_words) {
-    if (!p || (native != 1 && native != 2)) return UBP_ERR_INVALID_ARG;
+    if (!p || native < 1 || native > 3) return UBP_ERR_INVALID_ARG;
+    if (native == 3) {
+        // the dense operand tiles: row_groups = stripes, stream = the tiles as 32-bit words
+        const ubp::TileLayout &T = p->tiles;
+        if (T.kt_pad == 0) return UBP_ERR_UNSUPPORTED;
+        if (row_groups) *row_groups = T.nstripes;
+        if (rg_ptr) *rg_ptr = nullptr;
+        if (rg_order) *rg_order = nullptr;
+        if (stream) *stream = reinterpret_cast<const uint32_t *>(T.frags.data());
+        if (stream_words) *stream_words = (int64_t)(T.frags.size() / 2);
+        return UBP_OK;
+    }
     const int slot = ubp::layout_slot(sub_stripes, col_tiles);
     if (slot < 0) return UBP_ERR_INVALID_ARG;
     const ubp::StripeLayout &L = native == 2 ? p->sgn[slot] : p->sg[slot];
@@ -582,13 +593,16 @@ static void build_one(ubp_packed *p, StripeLayout &L, int G, int CT, bool native
 static void build_tiles(ubp_packed *p) {
     TileLayout &T = p->tiles;
     T.kt_pad = 0;
-    if (p->K > kTileMaxK) return;
     const int M = p->M, K = p->K, bh = p->bh, bw = p->bw;
     const int kt = (K + kStep - 1) / kStep;
-    T.kt_pad = std::max(2, ((kt + 1) / 2) * 2);
-    T.nstripes = (M + kStripe - 1) / kStripe;
+    // K <= 256: 2, 4, 6 or 8 tiles per stripe (held in registers at once); beyond that whole chunks
+    // of 8 tiles, while the zero-filled matrix stays small
+    const int kt_pad = K <= kTileMaxK ? std::max(2, ((kt + 1) / 2) * 2) : ((kt + 7) / 8) * 8;
+    const int nstripes = (M + kStripe - 1) / kStripe;
+    if ((int64_t)nstripes * kt_pad * 1024 > kTileMaxBytes) return;
+    T.kt_pad = kt_pad;
+    T.nstripes = nstripes;
     T.frags.assign((size_t)T.nstripes * T.kt_pad * 512, 0);
-    T.masks.assign((size_t)T.nstripes, 0u);
     const uint16_t *vals = reinterpret_cast<const uint16_t *>(p->values.data());
     const int32_t nstart = M - bh + 1;
     for (int i = 0; i < nstart; ++i)
@@ -602,7 +616,6 @@ static void build_tiles(ubp_packed *p) {
                     const int stripe = rho / kStripe, n = rho % kStripe;
                     const uint16_t v = vals[((int64_t)b * bw + q) * bh + (rho % bh)]; // rotated storage
                     T.frags[(((size_t)stripe * T.kt_pad + t) * 64 + (size_t)(16 * g + n)) * 8 + e] = v;
-                    T.masks[(size_t)stripe] |= 1u << t;
                 }
             }
         }

@@ -83,20 +83,21 @@ struct StripeLayout {
     int64_t total_mfma = 0; // MFMA issues per 16-column tile (steps x stripes with weights)
 };
 
-// Host image of the small-K kernel's layout: W as 16-row x 32-column operand tiles in MFMA
-// operand order, zeros where nothing is kept, for every (stripe, 32-column tile) pair, plus one
-// bit per pair that says whether the tile holds any kept weight (tiles without are skipped).
-// Built when K <= kTileMaxK; kt_pad = number of 32-column tiles rounded up to 2, 4, 6 or 8.
+// Host image of the dense-tile kernels' layout: W as 16-row x 32-column operand tiles in MFMA
+// operand order, zeros where nothing is kept, for every (stripe, 32-column tile) pair.
+// kt_pad = 32-column tiles per stripe: for K <= kTileMaxK rounded up to 2, 4, 6 or 8 (such a
+// stripe's tiles and a pixel block's X fit a wavefront's registers at once); for larger K
+// rounded up to a multiple of 8 (chunks of 256 rows), built only while the zero-filled matrix
+// stays below kTileMaxBytes.
 constexpr int kTileMaxK = 256;
+constexpr int64_t kTileMaxBytes = 8 << 20;
 struct TileLayout {
     int kt_pad = 0;                  // 0: not built
     int nstripes = 0;
     std::vector<uint16_t> frags;     // [nstripes][kt_pad][64 lanes][8]
-    std::vector<uint32_t> masks;     // [nstripes]
 };
 struct TileLayoutDev {
     uint16_t *frags = nullptr;
-    uint32_t *masks = nullptr;
 };
 
 struct StripeLayoutDev {

@@ -277,6 +277,56 @@ def test_private_layouts_decode_to_the_dense_matrix(shape, dtype):
     p.free()
 
 
+def _decode_tiles(p, M, K):
+    """Dense W (16-bit patterns) back from the operand tiles of the dense-tile kernels, from the
+    lane order the header documents: lane 16 g + n of a tile = row n of the stripe, columns
+    4 g .. 4 g + 3 and 16 + 4 g .. of the tile's 32."""
+    _, _, T = p.layout(0, 0, 3)
+    nstripes, kt_pad = T.shape[:2]
+    assert nstripes == (M + 15) // 16 and kt_pad * 32 >= K
+    Wd = np.zeros((nstripes * 16, kt_pad * 32), dtype=np.uint16)
+    for g in range(4):
+        for e in range(8):
+            col = 4 * g + e if e < 4 else 16 + 4 * g + (e - 4)
+            # T[:, :, 16 g : 16 g + 16, e] is [stripe][tile][n]
+            Wd.reshape(nstripes, 16, kt_pad, 32)[:, :, :, col] = T[:, :, 16 * g:16 * g + 16, e].transpose(0, 2, 1)
+    assert not Wd[M:].any() and not Wd[:, K:].any()     # the padding is zero
+    return Wd[:M, :K], kt_pad
+
+
+TILE_LAYOUT_SHAPES = [(64, 64, 4, 4, 0.5), (100, 200, 8, 8, 0.2), (130, 256, 16, 16, 0.15), (33, 40, 5, 3, 0.3),
+                      (257, 31, 1, 1, 0.3), (90, 300, 20, 3, 0.25), (250, 1000, 8, 8, 0.2), (40, 2100, 4, 4, 0.02)]
+
+
+@pytest.mark.parametrize("shape", TILE_LAYOUT_SHAPES, ids=lambda s: "x".join(map(str, s)))
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+def test_operand_tiles_decode_to_the_dense_matrix(shape, dtype):
+    M, K, bh, bw, d = shape
+    blocks = select_blocks(M, K, bh, bw, d, 78 + M, "uniform", 1.1)
+    W = make_weights(M, K, 6, dtype)
+    dense_bits = W.view(np.uint16).copy()
+    dense_bits[oracle.densify(np.ones((M, K)), bh, bw, blocks) == 0] = 0
+    p = ubp.pack(W, dtype, bh, bw, blocks, device=ubp.HOST_ONLY)
+    Wd, kt_pad = _decode_tiles(p, M, K)
+    assert np.array_equal(Wd, dense_bits)
+    # tiles per stripe: 2, 4, 6 or 8 up to K = 256, whole chunks of 8 beyond
+    assert kt_pad == (max(2, 2 * ((K + 63) // 64)) if K <= 256 else 8 * ((K + 255) // 256))
+    p.free()
+
+
+def test_operand_tiles_are_not_built_for_large_matrices_or_fp32():
+    blocks = select_blocks(4096, 2048, 16, 16, 0.01, 5, "uniform", 1.1)       # 256 stripes x 64 tiles = 16 MB
+    p = ubp.pack(make_weights(4096, 2048, 7, "bf16"), "bf16", 16, 16, blocks, device=ubp.HOST_ONLY)
+    with pytest.raises(ubp.UBPError):
+        p.layout(0, 0, 3)
+    p.free()
+    blocks = select_blocks(64, 64, 4, 4, 0.3, 5, "uniform", 1.1)
+    p = ubp.pack(make_weights(64, 64, 7, "f32"), "f32", 4, 4, blocks, device=ubp.HOST_ONLY)
+    with pytest.raises(ubp.UBPError):
+        p.layout(0, 0, 3)
+    p.free()
+
+
 @pytest.mark.parametrize("cfg", [c for c in CONFIGS if c.dtype != "f32"], ids=lambda c: c.name)
 def test_benchmark_layer_layouts_decode_to_the_dense_matrix(cfg):
     """The layouts the benchmark layers actually run with (and the block-native alternative)."""
@@ -289,4 +339,6 @@ def test_benchmark_layer_layouts_decode_to_the_dense_matrix(cfg):
     for g, ct, native in [(G, 8, 1), (G, 2, 1), (max(G, 2), 8, 2)]:
         Wd, _ = _decode_layout(p, g, ct, native, cfg.M, cfg.K, cfg.bh)
         assert np.array_equal(Wd, dense_bits), (g, ct, native)
+    if cfg.name != "c4":                                 # (c4's zero-filled matrix would be 32 MB: not built)
+        assert np.array_equal(_decode_tiles(p, cfg.M, cfg.K)[0], dense_bits)
     p.free()

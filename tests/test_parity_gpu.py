@@ -143,6 +143,43 @@ def test_x_stationary_kernel_small_k(shape, dtype):
     assert np.array_equal(Ya, Yt)
 
 
+CHUNK_SHAPES = [(64, 300, 200, 4, 4, 0.3), (250, 1000, 136, 8, 8, 0.2), (40, 257, 72, 5, 3, 0.3), (530, 600, 64, 16, 16, 0.15),
+                (16, 512, 16, 16, 16, 0.4), (100, 256, 40, 4, 4, 0.3), (256, 2304, 192, 4, 4, 0.25)]
+
+
+@pytest.mark.parametrize("shape", CHUNK_SHAPES, ids=lambda s: "x".join(map(str, s)))
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+def test_chunked_x_stationary_kernel(shape, dtype):
+    """The dense-tile kernel for K beyond 256 (X passes through the registers in chunks of 256
+    rows, accumulators stay): K a multiple of the chunk and not, one chunk only, more stripes
+    than a workgroup holds (slices), a last slice with fewer stripes than wavefronts, a pixel
+    block that hangs over the right edge, more slices than needed."""
+    M, K, N, bh, bw, d = shape
+    blocks, W, X = _layer(M, K, N, bh, bw, d, dtype, seed=M + K + 5)
+    Yref, Yabs = _oracle(W, dtype, bh, bw, blocks, X)
+    for CT, slices, SW in [(4, 0, 0), (2, 0, 0), (4, 5, 4), (2, 100, 4), (4, 0, 2), (2, 3, 2)]:
+        for y_dtype in (dtype, "f32"):
+            Y = run_spmm(W, dtype, bh, bw, blocks, X, y_dtype,
+                         _plan(kernel=5, col_tiles=CT, wg_rows=slices, sub_stripes=SW))
+            check(Y, Yref, Yabs, dtype, y_dtype)
+
+
+def test_chunked_kernel_refuses_what_it_cannot_do():
+    blocks, W, X = _layer(64, 160, 64, 4, 4, 0.3, "bf16", seed=5)        # 5 tiles per stripe: not whole chunks
+    with pytest.raises(ubp.UBPError):
+        run_spmm(W, "bf16", 4, 4, blocks, X, "bf16", _plan(kernel=5))
+    blocks, W, X = _layer(64, 512, 66, 4, 4, 0.3, "bf16", seed=6)        # N not a multiple of 8
+    with pytest.raises(ubp.UBPError):
+        run_spmm(W, "bf16", 4, 4, blocks, X, "bf16", _plan(kernel=5))
+    blocks, W, X = _layer(64, 512, 64, 4, 4, 0.3, "bf16", seed=7)
+    for bad in (dict(col_tiles=8), dict(waves=4), dict(sub_stripes=1)):
+        with pytest.raises(ubp.UBPError):
+            run_spmm(W, "bf16", 4, 4, blocks, X, "bf16", _plan(kernel=5, **bad))
+    blocks, W, X = _layer(64, 512, 64, 4, 4, 0.3, "f32", seed=8)
+    with pytest.raises(ubp.UBPError):
+        run_spmm(W, "f32", 4, 4, blocks, X, "f32", _plan(kernel=5))
+
+
 @pytest.mark.parametrize("kernel", [3, 4])
 def test_small_k_kernels_refuse_what_they_cannot_do(kernel):
     blocks, W, X = _layer(64, 300, 64, 4, 4, 0.3, "bf16", seed=5)       # K too large
