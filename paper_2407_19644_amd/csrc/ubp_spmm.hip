@@ -1023,19 +1023,20 @@ __global__ __launch_bounds__(512) void xstat_kernel(TileArgs a) {
 
 // ------------------------------------------------------------------ the same for larger K, in chunks
 // xstat_kernel's scheme when K does not fit the registers: K is cut into chunks of KT * 32 rows,
-// and what stays put are the accumulators - every multiplying wavefront owns SW stripes for the
-// whole of K (8 * SW stripes per workgroup: layers with few output rows, or slices of more).
-//  * 8 wavefronts multiply, 4 more do nothing but bring X in: global -> registers -> LDS
+// and what stays put are the accumulators - a workgroup owns 16 stripes x 16 * CT pixels for the
+// whole of K (layers with few output rows, or slices of more), a multiplying wavefront SW of
+// the stripes.
+//  * 16 / SW wavefronts multiply, 4 more do nothing but bring X in: global -> registers -> LDS
 //    (operand order, as above), requested four chunks ahead.  Separate wavefronts because a
 //    wavefront's vector memory operations complete in order: a weight tile from L2 requested
 //    behind rows of X from HBM is not seen before those have landed.
-//  * LDS holds a ring of kChunkRing chunks.  No barrier after start-up: each producer counts the
-//    chunks it has written, each multiplying wavefront the chunks it has read (every one reads
-//    every chunk), a slot is rewritten when all have read it.  The wavefronts may drift apart by
-//    the ring: with a barrier per chunk everybody would wait for its weight tiles at the same
-//    time and nothing would cover that wait (measured: 32 us instead of ... on the
-//    3x3-convolution layer).  Every wait is bounded; one that runs out raises the handle's
-//    error flag and the kernel finishes.
+//  * LDS holds a ring of kChunkRing chunks.  No barrier after start-up: each loading wavefront
+//    counts the chunks it has written, each multiplying wavefront the chunks it has read (every
+//    one reads every chunk), a slot is rewritten when all have read it.  The wavefronts may
+//    drift apart by the ring: with a barrier per chunk everybody would wait for its weight tiles
+//    at the same moment and nothing would cover that wait (measured on the 3x3-convolution
+//    layer: 32 us with barriers, 28.5 us without).  Every wait is bounded; one that runs out
+//    raises the handle's error flag and the kernel finishes.
 //  * A multiplying wavefront fetches the weight tiles of its own stripes straight from memory,
 //    two (stripe, chunk) sets ahead, in three register sets that rotate; its accumulator tiles
 //    leave at the end, through the wavefront's LDS rows.
