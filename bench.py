@@ -225,7 +225,7 @@ def main():
         "value": head["gflops_kept"], "unit": "GFLOP/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": head["ms_per_step"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": {"f32": "f32", "f16": "f16", "bf16": "bf16"}[cfg.dtype] + " in, f32 accumulate",
+        "dtype": cfg.dtype,          # multiplications in this type on the matrix cores, sums in f32
         "data": "synthetic",
         "config": {k: head[k] for k in ("workload", "what", "M", "K", "N", "block", "density", "nb", "in_dtype",
                                         "y_dtype", "cache", "buffer_sets", "graph")},
