@@ -219,13 +219,17 @@ constexpr int kSpinLimit = 1 << 22; // polls before a wait gives up (each poll i
 
 // The gather of step s+1 is issued before the MFMAs of step s (two operand buffers) except
 // for the largest tile, where the second buffer would halve the wavefronts per SIMD.
-constexpr bool stripe_pipelined(int G, int CT, bool NATIVE) { return NATIVE || G * CT < 32; }
+constexpr bool stripe_pipelined(int G, int CT, bool NATIVE) { return NATIVE ? G * CT != 16 : G * CT < 32; }
 
 constexpr int stripe_max_threads(int G, int CT, int D, bool NATIVE) {
     // accumulators + operand buffer(s) + D prefetched step records + addressing, in VGPRs
     // per lane; 512 per SIMD lane are shared by the wavefronts resident on the SIMD
     const int regs = 4 * G * CT + (stripe_pipelined(G, CT, NATIVE) ? 8 : 4) * CT + D * (2 + 4 * (NATIVE ? 1 : G)) +
                      (NATIVE ? 28 : G == 1 ? 8 : 20);
+    // (the estimate runs high for the block-native kernel, whose fragment registers are shared by the
+    // stripes: its limits are set from the compiled register counts, 123 / 138 for the two shapes
+    // that change tier)
+    if (NATIVE) return regs <= 136 ? 1024 : regs <= 190 ? 768 : 512;
     return regs <= 128 ? 1024 : regs <= 256 ? 512 : 256;
 }
 
@@ -1720,10 +1724,21 @@ ubp_status ubp_spmm_plan(const ubp_packed *p, const void *X_dev, int64_t ldx, in
     if (NP != 0 && NP != 1 && NP != 2 && NP != 4) return UBP_ERR_UNSUPPORTED;
     int native_req = pl.native ? pl.native : env_int("UBP_NATIVE", 0); // 0 auto, 1 merged columns, 2 block-native
     if (native_req < 0 || native_req > 2) return UBP_ERR_INVALID_ARG;
-    const bool native = native_req == 2; // (auto = merged columns: the shared operand costs more vector ALU work
-                                         //  per step than the smaller records save)
-    const StripeLayout *layouts = native ? p->sgn : p->sg;
     if ((G != 0 && G != 1 && G != 2 && G != 4) || (CT != 0 && CT != 2 && CT != 4 && CT != 8)) return UBP_ERR_UNSUPPORTED;
+    // Block-native records by themselves only for 16-row blocks, where a block fills the shared
+    // operand (shorter blocks leave rows of it empty), and then with 4 stripes x 4 column tiles per
+    // wavefront: that shape fits 128 registers, so a workgroup has 14 consumers instead of 6 and X
+    // is staged for 5 workgroup rows instead of 11 (largest layer: 159 us against 187 us for the
+    // best merged shape).  Elsewhere the shared operand costs more vector ALU work per step
+    // than the smaller records save.
+    bool native = native_req == 2;
+    if (native_req == 0 && p->bh == kStripe && (G == 0 || G == 4) && (CT == 0 || CT == 4) && N % 64 == 0 && N / 64 >= 32 &&
+        p->sgn[layout_slot(4, 4)].G != 0 && p->sgn[layout_slot(4, 4)].nch > ring_slots(4)) {
+        native = true;
+        G = 4;
+        CT = 4;
+    }
+    const StripeLayout *layouts = native ? p->sgn : p->sg;
     // Tile shape, from measurements on the four benchmark layers.
     //  * Column tiles as wide as divides N (a ragged last tile takes the slow staging path),
     //    provided that still leaves a few dozen tiles: wide tiles amortise a step's fixed
