@@ -141,19 +141,21 @@ ubp_status ubp_spmm(const ubp_packed *p, const void *X_dev, int64_t ldx, int32_t
  *                stay (sub_stripes 2 or 4 = stripes per multiplying wavefront; waves fixed).
  *                0 picks 1 for fp32; 4 for K <= 256; 5 for larger K when at least a fifth of W is
  *                kept; else 2.
- *   sub_stripes: MFMA kernel, 16-row stripes per wavefront (1, 2 or 4).
- *   col_tiles  : MFMA kernel, 16-column tiles per wavefront (2, 4 or 8).
- *   waves      : wavefronts per workgroup (MFMA kernel: producers + 1 .. 16).
- *   rows_per_range : WROS kernel, output rows owned by one workgroup row (multiple of bh).
- *   producers  : MFMA kernel, wavefronts of a workgroup that stage X into LDS (1, 2 or 4);
+ *   sub_stripes: kernel 2, 16-row stripes per wavefront (1, 2 or 4); kernel 5: 2 or 4.
+ *   col_tiles  : kernel 2, 16-column tiles per wavefront (2, 4 or 8); kernels 3 to 5: 2 or 4.
+ *   waves      : wavefronts per workgroup (kernel 2: producers + 1 .. 16, fewer for shapes that
+ *                need many registers; kernels 3 and 4 as above).
+ *   rows_per_range : kernel 1, output rows owned by one workgroup row (multiple of bh).
+ *   producers  : kernel 2, wavefronts of a workgroup that stage X into LDS (1, 2 or 4);
  *                the others each own a row group.
- *   wg_rows    : MFMA kernel, workgroups that share one column tile (each takes a share of
+ *   wg_rows    : kernel 2, workgroups that share one column tile (each takes a share of
  *                the row groups).  Free only when the staged tile holds all K rows of X at
  *                once (K <= 4096 / col_tiles); otherwise it must be 0 or
- *                ceil(row groups / (waves - producers)).
- *   native     : MFMA kernel, private weight layout: 1 = columns of all blocks of a row group
+ *                ceil(row groups / (waves - producers)).  Kernels 3 to 5: slices, as above.
+ *   native     : kernel 2, private weight layout: 1 = columns of all blocks of a row group
  *                merged, one operand per stripe; 2 = block-native, whole blocks and one operand
  *                shared by the stripes (needs bh <= 16, bw in {4, 8, 16, 32}, sub_stripes > 1).
+ *                0 picks 2 (with 4 stripes x 4 column tiles) for 16-row blocks on large K, else 1.
  */
 typedef struct {
     int32_t kernel, sub_stripes, col_tiles, waves, rows_per_range, producers, wg_rows, native;
@@ -166,8 +168,9 @@ ubp_status ubp_spmm_plan(const ubp_packed *p, const void *X_dev, int64_t ldx, in
 /*
  * Synchronous health check (copies one word from the device, so it waits for the work queued
  * before it on the NULL stream's terms; call it after synchronising the stream you used).
- * Every wait inside the MFMA kernel is bounded; a wait that runs out sets a bit here and the
- * kernel finishes with undefined Y instead of hanging.  *flags == 0 means no such event since
+ * Every wait inside kernels 2 and 5 (the ones whose wavefronts hand data to each other through
+ * LDS without barriers) is bounded; a wait that runs out sets a bit here and the kernel finishes
+ * with undefined Y instead of hanging.  *flags == 0 means no such event since
  * the handle was packed.
  */
 ubp_status ubp_packed_device_error(const ubp_packed *p, uint32_t *flags);
