@@ -219,6 +219,9 @@ constexpr int kSpinLimit = 1 << 22; // polls before a wait gives up (each poll i
 
 // The gather of step s+1 is issued before the MFMAs of step s (two operand buffers) except
 // for the largest tile, where the second buffer would halve the wavefronts per SIMD.
+// (The block-native 16-tile shape goes without the second buffer too: with it the shape needs
+// 139 registers, without it 123 - 16 wavefronts per workgroup instead of 12, 158 us against 173 us on
+// the largest layer.  Two records in flight instead of four would also make room, and cost 40 %.)
 constexpr bool stripe_pipelined(int G, int CT, bool NATIVE) { return NATIVE ? G * CT != 16 : G * CT < 32; }
 
 constexpr int stripe_max_threads(int G, int CT, int D, bool NATIVE) {
@@ -552,6 +555,12 @@ __global__ __launch_bounds__(stripe_max_threads(G, CT, D, NATIVE)) void stripe_k
                 issue(d);
                 __builtin_amdgcn_sched_barrier(0); // same issue order as in the loop, slot by slot
             }
+            // Wait for them here, with a wait the compiler sees.  It may keep these first records
+            // in other registers than the loop does and move them over; loads it believes pending
+            // on registers that the loop body writes (the operand buffers) then cost a wait for
+            // EVERYTHING in flight at the first step of every round of the loop - the record ring
+            // was being drained every D steps.  (vmcnt(0), other counters untouched.)
+            __builtin_amdgcn_s_waitcnt(0x0f70);
         }
     };
     start_stream();
