@@ -157,6 +157,8 @@ struct StripeArgs {
     int n_producers;         // producer wavefronts per workgroup: 1, 2 or 4 (the last wavefronts)
     int resident;            // the ring holds all of K: slots are never refilled, a consumer may walk several row groups
     int vec_ok;              // X and Y allow 16-byte vector access on every row
+    int out_bytes;           // LDS bytes per consumer behind the ring and the counters for 16 rows of a
+                             // 16-bit Y tile (stores then leave as whole rows of the tile); 0: none
     uint32_t *err;           // set to nonzero when a bounded wait runs out
 };
 
@@ -640,6 +642,40 @@ __global__ __launch_bounds__(stripe_max_threads(G, CT, D, NATIVE)) void stripe_k
         }
         // ---- store: lane (g = lane/16, n = lane%16) holds pixels col0 + 16*c + 4*g + v of row
         // 16*(G*rg + j) + n.  Rows no block touches are stored as zeros like any other.
+        if constexpr (sizeof(TY) == 2 && NATIVE) { // (NATIVE: the shapes with registers to spare for it)
+            if (a.out_bytes != 0) {
+                // A 16-bit tile straight from the accumulators is 8 bytes per lane, 32-byte runs per
+                // row.  Through 16 LDS rows of this wavefront (16-byte pieces XOR-swizzled by the row
+                // against bank conflicts; one wavefront writes and reads, LDS keeps its order) an
+                // instruction stores whole rows of the tile, 16 bytes per lane.
+                constexpr int RB = 16 * CT * 2;   // bytes per row of the tile: 64, 128 or 256
+                constexpr int PR = RB / 16;       // 16-byte pieces per row
+                constexpr int RP = 256 / RB;      // rows per 256 bytes (one pass over the banks)
+                constexpr int NI = PR / 4;        // store instructions per stripe
+                char *scratch = smem + a.ring_bytes + 32 * sizeof(uint32_t) + wave * a.out_bytes;
+#pragma unroll
+                for (int j = 0; j < G; ++j) {
+#pragma unroll
+                    for (int c = 0; c < CT; ++c) {
+                        typedef TY ty4 __attribute__((ext_vector_type(4)));
+                        ty4 o;
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) o[v] = from_f32<TY>(acc[j][c][v]);
+                        const int piece = (2 * c + (g >> 1)) ^ ((n / RP) & (PR - 1));
+                        *reinterpret_cast<ty4 *>(scratch + n * RB + piece * 16 + (g & 1) * 8) = o;
+                    }
+#pragma unroll
+                    for (int i = 0; i < NI; ++i) {
+                        const int r = i * (64 / PR) + lane / PR, lp = lane % PR;
+                        const uint4v o = *reinterpret_cast<const uint4v *>(scratch + r * RB + ((lp ^ ((r / RP) & (PR - 1))) << 4));
+                        const int row = (rg_done * G + j) * kStripe + r;
+                        if (row < a.M) *reinterpret_cast<uint4v *>(Yt + (int64_t)row * a.ldy + col0 + lp * 8) = o;
+                    }
+                }
+                if (!more) break;
+                continue;
+            }
+        }
 #pragma unroll
         for (int j = 0; j < G; ++j) {
             const int row = (rg_done * G + j) * kStripe + n;
@@ -1391,7 +1427,12 @@ ubp_status launch_xchunk(const TileArgs &a, int slices, hipStream_t st) {
 template <bool BF16, typename TY, int G, int CT, bool FAST, bool NATIVE>
 ubp_status launch_stripe_one(StripeArgs a, int ctile0, int n_coltiles, int waves, hipStream_t st) {
     constexpr int D = kPrefetchDepth;
-    const size_t lds = (size_t)a.ring_bytes + 32 * sizeof(uint32_t); // ring + the progress counters
+    // ring + the progress counters + (16-bit Y, full tiles only, where it fits) the consumers' output rows
+    if (FAST && NATIVE && sizeof(TY) == 2 && a.vec_ok) {
+        const size_t want = (size_t)16 * 16 * CT * 2;
+        if ((size_t)a.ring_bytes + 32 * sizeof(uint32_t) + (size_t)(waves - a.n_producers) * want <= 160 * 1024) a.out_bytes = (int)want;
+    }
+    const size_t lds = (size_t)a.ring_bytes + 32 * sizeof(uint32_t) + (size_t)(waves - a.n_producers) * a.out_bytes;
     static size_t attr_bytes = 0; // per instantiation; the limit is only ever raised
     if (lds > attr_bytes) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(&stripe_kernel<BF16, TY, G, CT, D, FAST, NATIVE>),
@@ -1833,6 +1874,7 @@ ubp_status ubp_spmm_plan(const ubp_packed *p, const void *X_dev, int64_t ldx, in
     a.n_producers = NP;
     a.resident = resident ? 1 : 0;
     a.vec_ok = vec_ok;
+    a.out_bytes = 0; // set per launch
     if (p->dtype == UBP_BF16)
         return y_dtype == UBP_F32 ? launch_stripe<true, float>(a, G, CT, native, waves, st)
                                   : launch_stripe<true, __bf16>(a, G, CT, native, waves, st);
