@@ -731,6 +731,7 @@ struct TileArgs {
     int M, K, N;
     int nstripes, sps;       // stripes in all, stripes per workgroup slice (<= SMAX)
     int n_blocks;            // pixel blocks (NW tiles each)
+    int slices;              // slices the stripes are cut into (xstat_kernel's workgroup order needs it)
     int kt_total;            // 32-column tiles per stripe in frags (xchunk_kernel: a multiple of its KT)
     uint32_t *err;           // the handle's error flags (bounded waits that ran out)
 };
@@ -923,7 +924,12 @@ __global__ __launch_bounds__(512) void xstat_kernel(TileArgs a) {
     const int NW = (int)(blockDim.x >> 6);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lane = threadIdx.x & 63;
-    const int block = blockIdx.x % a.n_blocks, slice = blockIdx.x / a.n_blocks;
+    // Consecutive workgroup ids go round-robin over the 8 XCDs: pixel blocks are dealt by id mod 8
+    // and the slices of a block are neighbours on its XCD, so that the block's X is fetched from
+    // memory once and found in that XCD's L2 by the other slices.
+    const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
+    const int block = xcd + 8 * (local / a.slices), slice = local % a.slices;
+    if (block >= a.n_blocks) return;
     const int bcol0 = block * 16 * CT;
 
     // the first stripe's weight tiles are on their way while X is loaded
@@ -1390,8 +1396,10 @@ template <bool BF16, typename TY, int CT, int KT>
 ubp_status launch_xstat_inst(const TileArgs &a, int waves, int slices, hipStream_t st) {
     // the X block, then 16 rows of output per wavefront: at most 32 + 32 KB, no attribute needed
     const size_t lds = (size_t)KT * CT * 1024 + (size_t)waves * 256 * CT * sizeof(TY);
-    hipLaunchKernelGGL((xstat_kernel<BF16, TY, CT, KT>), dim3((unsigned)(a.n_blocks * slices)), dim3((unsigned)waves * 64),
-                       lds, st, a);
+    TileArgs b = a;
+    b.slices = slices;
+    hipLaunchKernelGGL((xstat_kernel<BF16, TY, CT, KT>), dim3((unsigned)(8 * ((a.n_blocks + 7) / 8) * slices)),
+                       dim3((unsigned)waves * 64), lds, st, b);
     return hipGetLastError() == hipSuccess ? UBP_OK : UBP_ERR_DEVICE;
 }
 
@@ -1625,7 +1633,7 @@ ubp_status ubp_spmm_plan(const ubp_packed *p, const void *X_dev, int64_t ldx, in
         if (CT == 0) CT = 4;
         if (CT != 2 && CT != 4) return UBP_ERR_UNSUPPORTED;
         if (pl.waves != 0) return UBP_ERR_UNSUPPORTED; // fixed: 16 stripes' worth of multiplying wavefronts + 4 that load X
-        TileArgs a;
+        TileArgs a = {};
         a.frags = p->d_tiles.frags;
         a.X = static_cast<const uint16_t *>(X_dev);
         a.Y = Y_dev;
@@ -1668,7 +1676,7 @@ ubp_status ubp_spmm_plan(const ubp_packed *p, const void *X_dev, int64_t ldx, in
         // 64-pixel blocks halve the weight traffic per pixel; 32-pixel blocks where those would be few
         if (CT == 0) CT = N >= 128 * 64 ? 4 : 2;
         if (CT != 2 && CT != 4) return UBP_ERR_UNSUPPORTED;
-        TileArgs a;
+        TileArgs a = {};
         a.frags = p->d_tiles.frags;
         a.X = static_cast<const uint16_t *>(X_dev);
         a.Y = Y_dev;
@@ -1710,7 +1718,7 @@ ubp_status ubp_spmm_plan(const ubp_packed *p, const void *X_dev, int64_t ldx, in
         int waves = pl.waves ? pl.waves : env_int("UBP_WAVES", 0);
         if (waves == 0) waves = 8;
         if (waves != 1 && waves != 2 && waves != 4 && waves != 8) return UBP_ERR_UNSUPPORTED;
-        TileArgs a;
+        TileArgs a = {};
         a.frags = p->d_tiles.frags;
         a.X = static_cast<const uint16_t *>(X_dev);
         a.Y = Y_dev;
