@@ -164,6 +164,27 @@ def test_chunked_x_stationary_kernel(shape, dtype):
             check(Y, Yref, Yabs, dtype, y_dtype)
 
 
+def test_automatic_kernel_choice_for_large_k():
+    """What ubp_spmm picks by itself must be the documented kernel's result bit for bit: the
+    chunked dense-tile kernel when K > 256 and at least a fifth of W is kept, gathered rows
+    otherwise - with block-native records for 16-row blocks on a K that does not fit the ring."""
+    M, K, N, bh, bw = 160, 1100, 256, 4, 4
+    blocks, W, X = _layer(M, K, N, bh, bw, 0.25, "bf16", seed=91)
+    Ya = run_spmm(W, "bf16", bh, bw, blocks, X, "f32")
+    assert np.array_equal(Ya, run_spmm(W, "bf16", bh, bw, blocks, X, "f32", _plan(kernel=5)))
+    blocks, W, X = _layer(M, K, N, bh, bw, 0.1, "bf16", seed=92)          # too sparse for dense tiles
+    Ya = run_spmm(W, "bf16", bh, bw, blocks, X, "f32")
+    assert np.array_equal(Ya, run_spmm(W, "bf16", bh, bw, blocks, X, "f32", _plan(kernel=2)))
+    M, K, N, bh, bw = 256, 4608, 2048, 16, 16                             # 72 chunks of X against a ring of 16
+    blocks, W, X = _layer(M, K, N, bh, bw, 0.1, "bf16", seed=93)
+    Yref, Yabs = _oracle(W, "bf16", bh, bw, blocks, X)
+    Ya = run_spmm(W, "bf16", bh, bw, blocks, X, "f32")
+    check(Ya, Yref, Yabs, "bf16", "f32")
+    Yn = run_spmm(W, "bf16", bh, bw, blocks, X, "f32", _plan(kernel=2, sub_stripes=4, col_tiles=4, native=2))
+    assert np.array_equal(Ya, Yn)
+    check(run_spmm(W, "bf16", bh, bw, blocks, X, "bf16"), Yref, Yabs, "bf16")   # 16-bit tiles leave through LDS rows
+
+
 def test_chunked_kernel_refuses_what_it_cannot_do():
     blocks, W, X = _layer(64, 160, 64, 4, 4, 0.3, "bf16", seed=5)        # 5 tiles per stripe: not whole chunks
     with pytest.raises(ubp.UBPError):
