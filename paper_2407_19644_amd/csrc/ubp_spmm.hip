@@ -908,8 +908,8 @@ __global__ __launch_bounds__(512) void tile_kernel(TileArgs a) {
 //    stripe's loads are in flight while this stripe's KT*CT matrix instructions run, and the 16
 //    finished rows are stored at once.  Only CT accumulator tiles are alive at any time.
 // Pixels are dealt to the tiles so that a lane's results of two neighbouring tiles are 8
-// consecutive 16-bit pixels (one 16-byte store; the four lanes of a row then cover 64 bytes);
-// for a 32-bit Y a tile is 16 consecutive pixels.
+// consecutive 16-bit pixels (one 16-byte piece of the LDS rows through which a finished tile
+// leaves, see stripe_out); for a 32-bit Y a tile is 16 consecutive pixels.
 template <typename TY> struct PixelMap {
     // first pixel (in the block) of the 4 consecutive pixels that form piece p of tile c
     static constexpr bool kPairs = sizeof(TY) == 2;
