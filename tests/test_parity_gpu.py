@@ -164,6 +164,26 @@ def test_chunked_x_stationary_kernel(shape, dtype):
             check(Y, Yref, Yabs, dtype, y_dtype)
 
 
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+def test_dense_tile_kernels_with_padded_pitches(dtype):
+    """Kernels 3 to 5 on X and Y whose rows are longer than N (pitches that keep the rows 16-byte
+    aligned, as these kernels require): nothing may be read as data or written beyond column N,
+    and a ragged last pixel block must not spill into the padding."""
+    for M, K, N, bh, bw, d, kernels in [(100, 200, 200, 8, 8, 0.25, (3, 4)), (70, 256, 72, 4, 4, 0.3, (3, 4, 5)),
+                                        (150, 700, 136, 4, 4, 0.25, (5,))]:
+        blocks, W, X = _layer(M, K, N, bh, bw, d, dtype, seed=M + K + 6)
+        Yref, Yabs = _oracle(W, dtype, bh, bw, blocks, X)
+        for kernel in kernels:
+            for ldx, ldy in [(N + 8, N + 24), (N + 64, N), (N, N + 8)]:
+                for y_dtype in (dtype, "f32"):
+                    Y = run_spmm(W, dtype, bh, bw, blocks, X, y_dtype, _plan(kernel=kernel), ldx=ldx, ldy=ldy)
+                    check(Y, Yref, Yabs, dtype, y_dtype)
+        # pitches that break the alignment are refused by these kernels and served by the others
+        with pytest.raises(ubp.UBPError):
+            run_spmm(W, dtype, bh, bw, blocks, X, dtype, _plan(kernel=kernels[-1]), ldx=N + 4, ldy=N)
+        check(run_spmm(W, dtype, bh, bw, blocks, X, dtype, None, ldx=N + 4, ldy=N + 2), Yref, Yabs, dtype)
+
+
 def test_automatic_kernel_choice_for_large_k():
     """What ubp_spmm picks by itself must be the documented kernel's result bit for bit: the
     chunked dense-tile kernel when K > 256 and at least a fifth of W is kept, gathered rows
