@@ -330,6 +330,25 @@ def test_two_runs_are_bit_identical_and_columns_commute():
     assert np.array_equal(Y3, Y1[:, perm])
 
 
+@pytest.mark.parametrize("kernel", [2, 3, 4, 5])
+def test_every_mfma_kernel_is_deterministic_and_column_order_free(kernel):
+    """No kernel uses atomics on Y and every output element has one fixed summation order, whatever
+    the pace of the wavefronts that hand data to each other: repeated runs agree bit for bit, and
+    permuting the columns of X permutes the columns of Y."""
+    M, K, N, bh, bw = 144, 512, 384, 8, 8
+    blocks, W, X = _layer(M, K, N, bh, bw, 0.25, "bf16", seed=17)
+    if kernel in (3, 4):
+        K = 256
+        blocks, W, X = _layer(M, K, N, bh, bw, 0.25, "bf16", seed=18)
+    plan = _plan(kernel=kernel)
+    Y1 = run_spmm(W, "bf16", bh, bw, blocks, X, "f32", plan)
+    for _ in range(3):
+        assert np.array_equal(run_spmm(W, "bf16", bh, bw, blocks, X, "f32", plan), Y1)
+    perm = np.random.default_rng(1).permutation(N)
+    Yp = run_spmm(W, "bf16", bh, bw, blocks, np.ascontiguousarray(X[:, perm]), "f32", plan)
+    assert np.array_equal(Yp, Y1[:, perm])
+
+
 def test_device_errors_and_noop():
     cfg = get_config("c0")
     blocks, W, X = make_layer(cfg)
