@@ -144,7 +144,8 @@ def test_x_stationary_kernel_small_k(shape, dtype):
 
 
 CHUNK_SHAPES = [(64, 300, 200, 4, 4, 0.3), (250, 1000, 136, 8, 8, 0.2), (40, 257, 72, 5, 3, 0.3), (530, 600, 64, 16, 16, 0.15),
-                (16, 512, 16, 16, 16, 0.4), (100, 256, 40, 4, 4, 0.3), (256, 2304, 192, 4, 4, 0.25)]
+                (16, 512, 16, 16, 16, 0.4), (100, 256, 40, 4, 4, 0.3), (256, 2304, 192, 4, 4, 0.25),
+                (1000, 1500, 1000, 8, 8, 0.25)]
 
 
 @pytest.mark.parametrize("shape", CHUNK_SHAPES, ids=lambda s: "x".join(map(str, s)))
