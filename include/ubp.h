@@ -73,9 +73,9 @@ ubp_status ubp_select_reference(int32_t M, int32_t K, int32_t bh, int32_t bw, do
                                 ubp_block *out, int64_t capacity, int64_t *out_nb);
 
 /*
- * Offline weight transform (Section 4.2, "performed offline"): dense W + block list ->
- * the WROS sparse format, and, unless device == UBP_HOST_ONLY, its upload to that HIP
- * device (ordinal) together with the kernel's private re-layouts.
+ * Offline weight transform (Section 4.2; it runs once per layer, before inference): dense W +
+ * block list -> the WROS sparse format, and, unless device == UBP_HOST_ONLY, its upload to that
+ * HIP device (ordinal).
  *
  *   W_host : row-major M x K, leading dimension ldw (elements, >= K), element type dtype.
  *            Only the cells inside blocks are read.
@@ -90,6 +90,9 @@ ubp_status ubp_select_reference(int32_t M, int32_t K, int32_t bh, int32_t bw, do
  *   values [nb*bw*bh]     : values[(b*bw + q)*bh + s] = W[rho][c_b + q] where rho is the
  *                           row of block b with rho mod bh == s  (weight rotation: the
  *                           weight of output channel i sits in slot i mod bh).
+ * The kernels read private re-layouts derived from these arrays.  A re-layout is built and
+ * uploaded when the first product that needs it is prepared or run (ubp_spmm_prepare,
+ * ubp_spmm, ubp_spmm_plan); a handle holds only the ones that were used.
  * On error *out is NULL.  Free with ubp_packed_free.
  */
 ubp_status ubp_pack(const void *W_host, ubp_dtype dtype, int32_t M, int32_t K, int64_t ldw,
@@ -112,12 +115,22 @@ const void *ubp_packed_values(const ubp_packed *p, int64_t *len_elems);
  *           rounded to nearest-even once, at the store).  Every element of the M x N
  *           result is overwritten, rows no block touches with +0.  X and Y must not alias.
  *   hip_stream : a hipStream_t (NULL = the default stream).  The call only enqueues
- *           kernels on that stream: it never synchronises, allocates or copies.
+ *           kernels on that stream and never synchronises.
+ * Allocation: the FIRST call for a given kernel choice (which depends on N and on the
+ * alignment of the pointers and pitches) builds and uploads that kernel's re-layout of W - it
+ * allocates host and device memory and copies synchronously - and raises the kernel's LDS limit.
+ * Every later call with the same choice does neither.  Call ubp_spmm_prepare with the same
+ * arguments beforehand (for instance before capturing the stream into a graph) to have all of
+ * that done up front.
  * N == 0 is a no-op.  Errors: UBP_ERR_INVALID_ARG (null pointer, N < 0, pitch < N,
  * host-only handle, y_dtype neither fp32 nor the handle's dtype), UBP_ERR_UNSUPPORTED,
- * UBP_ERR_DEVICE (launch failed).  Nothing is written to Y on error.
- * Non-finite X: a zero weight the kernel pads with still multiplies X, so Inf/NaN in X can
- * reach outputs whose exact sum does not contain them.
+ * UBP_ERR_ALLOC, UBP_ERR_DEVICE (launch failed).  Nothing is written to Y on error.
+ * Non-finite X: the MFMA kernels multiply whole operand tiles, zero weights included.  An Inf
+ * or NaN in a row of X therefore reaches (as NaN) outputs whose exact sum does not contain it:
+ * with kernels 4 and 5, every output row whose 16-row stripe keeps a weight within the aligned
+ * 32 rows of X around it; with kernel 2, every row of a row group that keeps a weight in that
+ * column; with kernel 6, every row of a stripe that a block reaches into whose 16-row window of X
+ * (its columns, moved left at the right edge) contains it.  Kernel 1 multiplies kept weights only.
  */
 ubp_status ubp_spmm(const ubp_packed *p, const void *X_dev, int64_t ldx, int32_t N,
                     void *Y_dev, int64_t ldy, ubp_dtype y_dtype, void *hip_stream);
@@ -126,39 +139,41 @@ ubp_status ubp_spmm(const ubp_packed *p, const void *X_dev, int64_t ldx, int32_t
  * Same product with the kernel choice pinned (tests and tuning).  Fields set to 0 mean
  * "choose automatically"; an impossible combination returns UBP_ERR_UNSUPPORTED.
  *   kernel     : 1 = vector-ALU kernel that follows the WROS dataflow literally (any
- *                dtype, bh <= 16); 2 = MFMA kernel on aligned 16-row stripes that gathers the
- *                rows of X a row group needs (f16 / bf16); 3, 4 and 5 = MFMA kernels that use W
- *                as zero-filled 16 x 32 operand tiles (f16 / bf16, N a multiple of 8, 16-byte
+ *                dtype, bh <= 16).
+ *                2 = MFMA kernel on aligned 16-row stripes that gathers the rows of X a row
+ *                group needs (f16 / bf16).
+ *                4 and 5 = MFMA kernels that use W as zero-filled 16 x 32 operand tiles, skipping
+ *                tiles that keep nothing (f16 / bf16, N a multiple of 8, 16-byte
  *                aligned rows of X and Y; col_tiles 2 or 4; wg_rows = slices the stripes are
  *                cut into, one workgroup per slice and pixel block).
- *                3 (K <= 256) keeps all stripes of a slice in accumulators and passes X through
- *                LDS 32 rows at a time (waves 1, 2, 4 or 8 = neighbouring pixel tiles).
  *                4 (K <= 256) keeps the X of one pixel block in registers and streams the stripes
  *                past it, 16 finished rows at a time - the order of the paper's section 4.2
  *                (waves 1..8 share a slice's stripes).
  *                5 (any K whose zero-filled W stays below 8 MB) cuts K into chunks of 128 rows
  *                that pass through LDS and the registers while the accumulators of 16 stripes
  *                stay (sub_stripes 2 or 4 = stripes per multiplying wavefront; waves fixed).
- *                0 picks 1 for fp32; 4 for K <= 256; 5 for larger K when at least a fifth of W is
- *                kept; else 2.
- *   sub_stripes: kernel 2, 16-row stripes per wavefront (1, 2 or 4); kernel 5: 2 or 4.
- *   col_tiles  : kernel 2, 16-column tiles per wavefront (2, 4 or 8); kernels 3 to 5: 2 or 4.
- *   waves      : wavefronts per workgroup (kernel 2: producers + 1 .. 16, fewer for shapes that
- *                need many registers; kernels 3 and 4 as above).
+ *                6 = MFMA kernel with whole blocks as operands, stored by row modulo 16 - the
+ *                paper's rotation with period 16 (f16 / bf16, bh <= 16, 16 <= K < 65408, N >= 64,
+ *                16-byte aligned rows; col_tiles 4 only; sub_stripes 2, 4 or 5).
+ *                0 picks 1 for fp32; 6 for 16-row blocks at least 16 wide when K > 1024; else 4
+ *                (K <= 256) or 5 when at least half of the 16 x 32 tiles of W keep a weight; else 2.
+ *                (3 is not used.)
+ *   sub_stripes: kernels 2 and 6, 16-row stripes per wavefront (1, 2 or 4; kernel 6: 2, 4 or 5,
+ *                by itself 5 where that saves a workgroup row, else 4);
+ *                kernel 5: 2 or 4.
+ *   col_tiles  : kernel 2, 16-column tiles per wavefront (2, 4 or 8); kernels 4 and 5: 2 or 4.
+ *   waves      : wavefronts per workgroup (kernels 2 and 6: producers + 1 .. 16, fewer for shapes
+ *                that need many registers; kernel 4 as above).
  *   rows_per_range : kernel 1, output rows owned by one workgroup row (multiple of bh).
- *   producers  : kernel 2, wavefronts of a workgroup that stage X into LDS (1, 2 or 4);
+ *   producers  : kernels 2 and 6, wavefronts of a workgroup that stage X into LDS (1, 2 or 4);
  *                the others each own a row group.
- *   wg_rows    : kernel 2, workgroups that share one column tile (each takes a share of
- *                the row groups).  Free only when the staged tile holds all K rows of X at
- *                once (K <= 4096 / col_tiles); otherwise it must be 0 or
- *                ceil(row groups / (waves - producers)).  Kernels 3 to 5: slices, as above.
- *   native     : kernel 2, private weight layout: 1 = columns of all blocks of a row group
- *                merged, one operand per stripe; 2 = block-native, whole blocks and one operand
- *                shared by the stripes (needs bh <= 16, bw in {4, 8, 16, 32}, sub_stripes > 1).
- *                0 picks 2 (with 4 stripes x 4 column tiles) for 16-row blocks on large K, else 1.
+ *   wg_rows    : kernels 2 and 6, workgroups that share one column tile (each takes a share of
+ *                the row groups).  Free only for kernel 2 when the staged tile holds all K rows
+ *                of X at once (K <= 4096 / col_tiles); otherwise it must be 0 or
+ *                ceil(row groups / (waves - producers)).  Kernels 4 and 5: slices, as above.
  */
 typedef struct {
-    int32_t kernel, sub_stripes, col_tiles, waves, rows_per_range, producers, wg_rows, native;
+    int32_t kernel, sub_stripes, col_tiles, waves, rows_per_range, producers, wg_rows;
 } ubp_plan;
 
 ubp_status ubp_spmm_plan(const ubp_packed *p, const void *X_dev, int64_t ldx, int32_t N,
@@ -166,9 +181,21 @@ ubp_status ubp_spmm_plan(const ubp_packed *p, const void *X_dev, int64_t ldx, in
                          const ubp_plan *plan);
 
 /*
+ * Everything ubp_spmm_plan does with these arguments except the launch: resolves the kernel
+ * and its shape, builds and uploads the re-layout of W that shape reads (host and device
+ * allocation, synchronous copies) and raises the kernel's LDS limit.  X_dev and Y_dev are only
+ * looked at for their alignment.  plan may be NULL (automatic choice, as ubp_spmm).  If chosen
+ * is not NULL it receives the resolved shape, every field filled in as far as it applies.
+ * After it returns UBP_OK, ubp_spmm / ubp_spmm_plan with the same arguments allocate nothing.
+ */
+ubp_status ubp_spmm_prepare(const ubp_packed *p, const void *X_dev, int64_t ldx, int32_t N,
+                            void *Y_dev, int64_t ldy, ubp_dtype y_dtype, const ubp_plan *plan,
+                            ubp_plan *chosen);
+
+/*
  * Synchronous health check (copies one word from the device, so it waits for the work queued
  * before it on the NULL stream's terms; call it after synchronising the stream you used).
- * Every wait inside kernels 2 and 5 (the ones whose wavefronts hand data to each other through
+ * Every wait inside kernels 2, 5 and 6 (the ones whose wavefronts hand data to each other through
  * LDS without barriers) is bounded; a wait that runs out sets a bit here and the kernel finishes
  * with undefined Y instead of hanging.  *flags == 0 means no such event since
  * the handle was packed.
@@ -176,32 +203,57 @@ ubp_status ubp_spmm_plan(const ubp_packed *p, const void *X_dev, int64_t ldx, in
 ubp_status ubp_packed_device_error(const ubp_packed *p, uint32_t *flags);
 
 /*
- * Facts about a handle, for reporting.  what: 0 M, 1 K, 2 bh, 3 bw, 4 nb, 5 dtype,
- * 6 device (-1 host only), 7 bytes of the canonical arrays (values + indptr + indices),
- * 8 bytes of all device-side copies.  Unknown `what` returns -1.
+ * Facts about a handle, for reporting.  what:
+ *   0 M, 1 K, 2 bh, 3 bw, 4 nb, 5 dtype, 6 device (-1 host only),
+ *   7 bytes of the canonical arrays (values + indptr + indices),
+ *   8 bytes of all device-side copies made so far,
+ *   9 MFMA instructions (16 x 16 x 32) per 16 columns of X that the kept weights would fill
+ *     completely: ceil(nb * bh * bw / 512) - the yardstick for the counts below.
+ * The following describe private re-layouts and build the one they ask about (host memory
+ * only); -1 where it does not exist for this matrix (always for fp32):
+ *   10 / 11  dense operand tiles (kernels 4, 5): tiles that keep a weight = MFMAs issued per 16
+ *            columns / all 16 x 32 tiles of the matrix;
+ *   100 + s / 200 + s  gather layout s = 3 * log2(sub_stripes) + log2(col_tiles) - 1 (kernel 2):
+ *            MFMAs issued per 16 columns / steps;
+ *   300 + 3 i + g, block layout (kernel 6) for sub_stripes 2, 4, 5 (g = 0, 1, 2): i = 0 MFMAs
+ *            issued per 16 columns, 1 steps, 2 half-blocks placed, 3 half-blocks that share a step
+ *            with another.
+ * Unknown `what` returns -1.
  */
 int64_t ubp_packed_info(const ubp_packed *p, int32_t what);
 
 /*
- * Read-only view of one of the MFMA kernel's private weight layouts (host copies; valid
- * until ubp_packed_free), so that the host-side re-layout can be checked without a GPU:
- * decoding the step records must give back the dense matrix.  sub_stripes / col_tiles /
- * native name the layout as in ubp_plan (native: 1 merged columns, 2 block-native).
- *   rg_ptr   : int32[row groups + 1], first step record of each row group
- *   rg_order : int32[row groups], row groups by decreasing work
- *   stream   : uint32[stream_words], the step records (format: comment of StripeLayout in
- *              csrc/ubp_internal.h)
- * native = 3 views the dense operand tiles of kernels 3 to 5 instead (sub_stripes and col_tiles
- * are ignored): row_groups = number of 16-row stripes, rg_ptr = rg_order = NULL, stream =
- * [stripes][tiles per stripe][64 lanes][8] 16-bit weights as 32-bit words (tiles per stripe =
- * stream_words / (256 * stripes)); lane 16 g + n of a tile holds row n of the stripe, columns
- * 4 g .. 4 g + 3 and 16 + 4 g .. 16 + 4 g + 3 of the tile's 32.
- * Returns UBP_ERR_UNSUPPORTED when that layout was not built for this matrix (fp32, K too
- * large, block shape not eligible).  Any output pointer may be NULL.
+ * Read-only view of one of the MFMA kernels' private weight layouts (host copies, built on
+ * demand; valid until ubp_packed_free), so that the host-side re-layout can be checked without
+ * a GPU: decoding the records must give back the dense matrix.  Formats: comments of
+ * StripeLayout, BlkLayout and TileLayout in csrc/ubp_internal.h.
+ *   which = 1: gather layout (sub_stripes, col_tiles as in ubp_plan).  rg_ptr int32[row groups
+ *              + 1] first step record of each row group, rg_order int32[row groups] row groups
+ *              by decreasing work, stream uint32[stream_words] the step records.
+ *   which = 2: block layout (sub_stripes 2, 4 or 5; col_tiles ignored).  rg_ptr, rg_order as
+ *              above, stream = the operand records (256 words per step), meta = 2 words per step.
+ *   which = 3: the dense operand tiles (sub_stripes, col_tiles ignored).  row_groups = number
+ *              of 16-row stripes, rg_ptr = rg_order = NULL, stream = [stripes][tiles per
+ *              stripe][64 lanes][8] 16-bit weights as 32-bit words (tiles per stripe =
+ *              stream_words / (256 * stripes)); lane 16 g + n of a tile holds row n of the
+ *              stripe, columns 4 g .. 4 g + 3 and 16 + 4 g .. 16 + 4 g + 3 of the tile's 32;
+ *              meta = one bit per tile (bit t % 32 of word stripe * ceil(tiles per stripe / 32)
+ *              + t / 32): the tile keeps a weight.
+ * Returns UBP_ERR_UNSUPPORTED when that layout does not exist for this matrix (fp32, K too
+ * large, block shape not eligible).  Any output pointer may be NULL; meta / meta_words are set
+ * to NULL / 0 where a layout has none.
  */
-ubp_status ubp_packed_layout(const ubp_packed *p, int32_t sub_stripes, int32_t col_tiles, int32_t native,
+ubp_status ubp_packed_layout(const ubp_packed *p, int32_t sub_stripes, int32_t col_tiles, int32_t which,
                              int32_t *row_groups, const int32_t **rg_ptr, const int32_t **rg_order,
-                             const uint32_t **stream, int64_t *stream_words);
+                             const uint32_t **stream, int64_t *stream_words,
+                             const uint32_t **meta, int64_t *meta_words);
+
+/*
+ * Enqueues an empty kernel (one wavefront, no memory access) on hip_stream: what a launch costs
+ * on this device when there is nothing to do.  For measurement harnesses that report the
+ * launch floor next to layers whose HBM time is below it.
+ */
+ubp_status ubp_launch_floor(void *hip_stream);
 
 /* Releases host and device memory of the handle (NULL is allowed).  Must not be called
  * while a ubp_spmm using the handle is still running on the device. */

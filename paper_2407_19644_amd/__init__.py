@@ -4,4 +4,5 @@ Thin ctypes binding over the C ABI declared in include/ubp.h.  Everything is com
 the native library (host packer + HIP kernels); this package only marshals arguments.
 """
 from .binding import (UBPError, Packed, Plan, load_library, library_path, select_reference,  # noqa: F401
-                      target_block_count, pack, spmm, status_string, layout_slot, DTYPES, EXPORTS, HOST_ONLY)
+                      target_block_count, pack, spmm, spmm_prepare, launch_floor, status_string, layout_slot, DTYPES,
+                      EXPORTS, HOST_ONLY)

@@ -23,7 +23,8 @@ DTYPES = {"f32": 0, "f16": 1, "bf16": 2}
 _NP_OF = {"f32": np.float32, "f16": np.float16, "bf16": np.uint16}
 EXPORTS = ("ubp_target_block_count", "ubp_select_reference", "ubp_pack", "ubp_packed_indptr",
            "ubp_packed_indices", "ubp_packed_values", "ubp_spmm", "ubp_spmm_plan", "ubp_packed_info",
-           "ubp_packed_free", "ubp_status_string", "ubp_packed_device_error", "ubp_packed_layout")
+           "ubp_packed_free", "ubp_status_string", "ubp_packed_device_error", "ubp_packed_layout",
+           "ubp_spmm_prepare", "ubp_launch_floor")
 
 
 class UBPError(RuntimeError):
@@ -36,7 +37,7 @@ class Plan(ctypes.Structure):
     """Mirror of ubp_plan; zero fields mean 'choose automatically'."""
     _fields_ = [("kernel", ctypes.c_int32), ("sub_stripes", ctypes.c_int32), ("col_tiles", ctypes.c_int32),
                 ("waves", ctypes.c_int32), ("rows_per_range", ctypes.c_int32), ("producers", ctypes.c_int32),
-                ("wg_rows", ctypes.c_int32), ("native", ctypes.c_int32)]
+                ("wg_rows", ctypes.c_int32)]
 
 
 _lib = None
@@ -74,8 +75,12 @@ def load_library():
     L.ubp_packed_device_error.argtypes = [vp, ctypes.POINTER(ctypes.c_uint32)]
     L.ubp_packed_device_error.restype = ctypes.c_int
     L.ubp_packed_layout.argtypes = [vp, i32, i32, i32, ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(vp),
-                                    ctypes.POINTER(vp), ctypes.POINTER(vp), pi64]
+                                    ctypes.POINTER(vp), ctypes.POINTER(vp), pi64, ctypes.POINTER(vp), pi64]
     L.ubp_packed_layout.restype = ctypes.c_int
+    L.ubp_spmm_prepare.argtypes = [vp, vp, i64, i32, vp, i64, ctypes.c_int, ctypes.POINTER(Plan), ctypes.POINTER(Plan)]
+    L.ubp_spmm_prepare.restype = ctypes.c_int
+    L.ubp_launch_floor.argtypes = [vp]
+    L.ubp_launch_floor.restype = ctypes.c_int
     L.ubp_packed_free.argtypes = [vp]
     L.ubp_packed_free.restype = None
     L.ubp_status_string.argtypes = [ctypes.c_int]
@@ -123,14 +128,17 @@ class Packed:
     def info(self, what):
         return int(load_library().ubp_packed_info(self.handle, what))
 
-    def layout(self, sub_stripes, col_tiles, native=1):
-        """ubp_packed_layout -> (rg_ptr int32[nrg + 1], rg_order int32[nrg], stream uint32[...]) as copies;
-        native=3: the dense operand tiles as (None, None, uint16[stripes][tiles][64][8])."""
+    def layout(self, sub_stripes, col_tiles, which=1):
+        """ubp_packed_layout, as copies.  which=1 (gather layout): (rg_ptr int32[nrg + 1], rg_order
+        int32[nrg], stream uint32[...]); which=2 (block layout): (rg_ptr, rg_order, records
+        uint32[steps + spare][256], meta uint32[steps + spare][2]); which=3 (dense operand tiles):
+        (None, None, uint16[stripes][tiles][64][8], occupied uint32[stripes][words])."""
         nrg = ctypes.c_int32(0)
-        words = ctypes.c_int64(0)
-        a, b, c = ctypes.c_void_p(), ctypes.c_void_p(), ctypes.c_void_p()
-        rc = load_library().ubp_packed_layout(self.handle, sub_stripes, col_tiles, native, ctypes.byref(nrg),
-                                              ctypes.byref(a), ctypes.byref(b), ctypes.byref(c), ctypes.byref(words))
+        words, mwords = ctypes.c_int64(0), ctypes.c_int64(0)
+        a, b, c, m = ctypes.c_void_p(), ctypes.c_void_p(), ctypes.c_void_p(), ctypes.c_void_p()
+        rc = load_library().ubp_packed_layout(self.handle, sub_stripes, col_tiles, which, ctypes.byref(nrg),
+                                              ctypes.byref(a), ctypes.byref(b), ctypes.byref(c), ctypes.byref(words),
+                                              ctypes.byref(m), ctypes.byref(mwords))
         if rc != UBP_OK:
             raise UBPError(rc, "ubp_packed_layout")
 
@@ -139,10 +147,13 @@ class Packed:
                 return np.zeros(0, dtype=dt)
             buf = (ctypes.c_char * (n * np.dtype(dt).itemsize)).from_address(ptr.value)
             return np.frombuffer(buf, dtype=dt).copy()
-        if native == 3:   # dense operand tiles: (None, None, uint16[stripes][tiles][64][8])
+        if which == 3:
             t = copy(c, words.value, np.uint32).view(np.uint16)
-            return None, None, t.reshape(nrg.value, -1, 64, 8)
-        return (copy(a, nrg.value + 1, np.int32), copy(b, nrg.value, np.int32), copy(c, words.value, np.uint32))
+            return None, None, t.reshape(nrg.value, -1, 64, 8), copy(m, mwords.value, np.uint32).reshape(nrg.value, -1)
+        rg_ptr, rg_order = copy(a, nrg.value + 1, np.int32), copy(b, nrg.value, np.int32)
+        if which == 2:
+            return rg_ptr, rg_order, copy(c, words.value, np.uint32).reshape(-1, 256), copy(m, mwords.value, np.uint32).reshape(-1, 2)
+        return rg_ptr, rg_order, copy(c, words.value, np.uint32)
 
     def _view(self, fn, np_dtype):
         n = ctypes.c_int64(0)
@@ -209,3 +220,21 @@ def spmm(packed, X_ptr, ldx, N, Y_ptr, ldy, y_dtype, stream=0, plan=None):
         rc = L.ubp_spmm_plan(packed.handle, X_ptr, ldx, N, Y_ptr, ldy, DTYPES[y_dtype], stream, ctypes.byref(plan))
     if rc != UBP_OK:
         raise UBPError(rc, "ubp_spmm")
+
+
+def spmm_prepare(packed, X_ptr, ldx, N, Y_ptr, ldy, y_dtype, plan=None):
+    """ubp_spmm_prepare: everything ubp_spmm / ubp_spmm_plan would do with these arguments except
+    the launch.  Returns the resolved Plan."""
+    chosen = Plan()
+    rc = load_library().ubp_spmm_prepare(packed.handle, X_ptr, ldx, N, Y_ptr, ldy, DTYPES[y_dtype],
+                                         ctypes.byref(plan) if plan is not None else None, ctypes.byref(chosen))
+    if rc != UBP_OK:
+        raise UBPError(rc, "ubp_spmm_prepare")
+    return chosen
+
+
+def launch_floor(stream=0):
+    """ubp_launch_floor: an empty kernel on the stream."""
+    rc = load_library().ubp_launch_floor(stream)
+    if rc != UBP_OK:
+        raise UBPError(rc, "ubp_launch_floor")

@@ -166,16 +166,15 @@ def _ring_swizzle(CT, r):
     return ((r >> 2) & 1) if CT == 2 else ((r >> 1) & 3) if CT == 4 else (r & 7)
 
 
-def _decode_layout(packed, G, CT, native, M, K, bh):
-    """Replays what the MFMA kernel does with a layout's step records, on the host and for the
+def _decode_layout(packed, G, CT, M, K):
+    """Replays what the gather kernel does with a layout's step records, on the host and for the
     weights only: which X row every gathered entry is (ring address -> row, through the
     chunks the control words say are held) and which output rows every operand value feeds.
     Returns the dense matrix the records stand for (16-bit patterns) and the MFMA count."""
-    rg_ptr, rg_order, stream = packed.layout(G, CT, native)
+    rg_ptr, rg_order, stream = packed.layout(G, CT, 1)
     nrg = len(rg_order)
     assert sorted(rg_order.tolist()) == list(range(nrg))
-    FG = 1 if native == 2 else G
-    rec_dw = 128 + 256 * FG
+    rec_dw = 128 + 256 * G
     PITCH, RR = 32 * CT, 131072 // (32 * CT)
     R = RR // 64
     nch = -(-K // 64)
@@ -194,12 +193,8 @@ def _decode_layout(packed, G, CT, native, M, K, bh):
             d0, d1 = rec[0:128:2], rec[1:128:2]
             mask = int(d0[0] >> 28)
             assert np.all(d0 >> 28 == mask)
-            if native == 2:
-                ctl = int(sum(((int(d1[l]) >> 31) & 1) << l for l in range(32)))
-                assert np.all(d1[32:] >> 31 == 0)
-            else:
-                ctl = int(d1[0])
-                assert np.all(d1 == ctl)
+            ctl = int(d1[0])
+            assert np.all(d1 == ctl)
             need, rel = ctl & 0xffff, ctl >> 16
             assert prev_rel <= rel <= nch                    # chunks are handed back in order
             prev_rel = rel
@@ -221,21 +216,13 @@ def _decode_layout(packed, G, CT, native, M, K, bh):
             krow = np.zeros(32, dtype=np.int64)
             krow[idx_lo], krow[idx_hi] = ks[0], ks[1]
             assert np.array_equal(krow[idx_lo], ks[0]) and np.array_equal(krow[idx_hi], ks[1])
-            frag = rec[128:].view(np.uint16).reshape(FG, 64, 8)
+            frag = rec[128:].view(np.uint16).reshape(G, 64, 8)
             ent = np.concatenate([(4 * g)[:, None] + np.arange(4), (16 + 4 * g)[:, None] + np.arange(4)], axis=1)  # [64, 8]
             for j in range(G):
                 if not (mask >> j) & 1:
-                    if native != 2:
-                        assert not frag[j].any()
+                    assert not frag[j].any()
                     continue
-                vals = frag[0 if native == 2 else j].copy()
-                if native == 2:
-                    t_lo = (d1 & 0x7f).astype(np.int64) - 64
-                    t_hi = ((d1 >> 8) & 0x7f).astype(np.int64) - 64
-                    lo_ok = (t_lo + 16 * j >= 0) & (t_lo + 16 * j < bh)
-                    hi_ok = (t_hi + 16 * j >= 0) & (t_hi + 16 * j < bh)
-                    vals[~lo_ok, :4] = 0
-                    vals[~hi_ok, 4:] = 0
+                vals = frag[j]
                 rows = (rg * G + j) * 16 + t                                  # [64]
                 rr = np.repeat(rows[:, None], 8, axis=1)
                 kk = krow[ent]
@@ -246,9 +233,62 @@ def _decode_layout(packed, G, CT, native, M, K, bh):
     return Wd[:M], mfma
 
 
+def _decode_block_layout(packed, G, M, K):
+    """The same for the block kernel's layout: the window rows a lane reads (entry i of a half =
+    the window row congruent to i modulo 16), the stripe a row-slot's weight goes to (rows
+    n >= o: the stripe the block starts in, rows n < o: the next one), the chunks a step needs
+    against the chunks handed back.  Returns the dense matrix (16-bit patterns) and the MFMA count."""
+    rg_ptr, rg_order, recs, meta = packed.layout(G, 0, 2)
+    nrg = len(rg_order)
+    assert sorted(rg_order.tolist()) == list(range(nrg))
+    nsteps = int(rg_ptr[-1])
+    assert recs.shape == (nsteps + 4, 256) and meta.shape == (nsteps + 128, 2)
+    assert not recs[nsteps:].any() and not meta[nsteps:].any()
+    R, nch = 16, -(-K // 64)
+    lanes = np.arange(64)
+    g, n = lanes // 16, lanes % 16
+    Wd = np.zeros((nrg * 16 * G, K), dtype=np.uint16)
+    mfma = 0
+    for rg in range(nrg):
+        assert (rg_ptr[rg + 1] - rg_ptr[rg]) % 4 == 0
+        prev_rel = 0
+        for s in range(rg_ptr[rg], rg_ptr[rg + 1]):
+            m0, m1 = int(meta[s, 0]), int(meta[s, 1])
+            a = (m0 & 0xffff, m0 >> 16)
+            o = (m1 & 15, (m1 >> 4) & 15)
+            jj, do_lo, do_hi, rel = (m1 >> 8) & 15, (m1 >> 12) & 1, (m1 >> 13) & 1, m1 >> 22
+            assert (m1 >> 14) & 0xff == 0
+            assert prev_rel <= rel <= nch
+            prev_rel = rel
+            frag = recs[s].view(np.uint16).reshape(64, 8)
+            if jj == 15:
+                assert m0 == 0 and not frag.any() and not do_lo and not do_hi
+                continue
+            assert jj <= G and do_lo == (jj >= 1) and (do_lo or do_hi)
+            need = (max(a) + 15) >> 6
+            assert rel <= min(a) >> 6 and need < nch and need - rel <= R - 2
+            assert max(a) + 16 <= K
+            mfma += do_lo + do_hi
+            for e in range(8):
+                h = e // 4
+                i = 4 * g + (e & 3)
+                rho = a[h] + ((i - a[h]) % 16)                       # row of X per lane
+                v = frag[:, e]
+                lower = n >= o[h]                                      # rows that stay in stripe jj - 1
+                for part, stripe, on in ((lower, jj - 1, do_lo), (~lower, jj, do_hi)):
+                    sel = part & (v != 0)
+                    if not on or not 0 <= stripe < G:
+                        continue
+                    rows = (rg * G + stripe) * 16 + n[sel]
+                    assert not Wd[rows, rho[sel]].any()                # no weight is delivered twice
+                    Wd[rows, rho[sel]] = v[sel]
+    assert not Wd[M:].any()
+    return Wd[:M], mfma
+
+
 LAYOUT_SHAPES = [(64, 64, 4, 4, 0.5), (100, 300, 8, 8, 0.2), (130, 600, 16, 16, 0.15), (33, 40, 5, 3, 0.3),
                  (40, 2100, 4, 4, 0.02), (96, 2304, 4, 8, 0.1), (257, 31, 1, 1, 0.3), (90, 64, 20, 3, 0.25),
-                 (70, 4200, 16, 32, 0.08)]
+                 (70, 4200, 16, 32, 0.08), (150, 1300, 16, 40, 0.2), (64, 15, 8, 8, 0.2), (200, 3000, 12, 16, 0.1)]
 
 
 @pytest.mark.parametrize("shape", LAYOUT_SHAPES, ids=lambda s: "x".join(map(str, s)))
@@ -261,19 +301,20 @@ def test_private_layouts_decode_to_the_dense_matrix(shape, dtype):
     keep = oracle.densify(np.ones((M, K)), bh, bw, blocks) != 0
     dense_bits[~keep] = 0
     p = ubp.pack(W, dtype, bh, bw, blocks, device=ubp.HOST_ONLY)
-    eligible = bh <= 16 and bw in (4, 8, 16, 32)
     for G in (1, 2, 4):
         for CT in (2, 4, 8):
-            Wd, mfma = _decode_layout(p, G, CT, 1, M, K, bh)
+            Wd, mfma = _decode_layout(p, G, CT, M, K)
             assert np.array_equal(Wd, dense_bits), (G, CT)
             assert mfma == p.info(100 + ubp.layout_slot(G, CT))
-            if eligible and G > 1:
-                Wn, mfma_n = _decode_layout(p, G, CT, 2, M, K, bh)
-                assert np.array_equal(Wn, dense_bits), ("native", G, CT)
-                assert mfma_n == p.info(300 + ubp.layout_slot(G, CT))
-            else:
-                with pytest.raises(ubp.UBPError):
-                    p.layout(G, CT, 2)
+    for gi, G in enumerate((2, 4, 5)):
+        if bh <= 16 and K >= 16:
+            Wn, mfma_n = _decode_block_layout(p, G, M, K)
+            assert np.array_equal(Wn, dense_bits), ("block", G)
+            assert mfma_n == p.info(300 + gi)
+            assert p.info(309 + gi) <= p.info(306 + gi)
+        else:
+            with pytest.raises(ubp.UBPError):
+                p.layout(G, 0, 2)
     p.free()
 
 
@@ -281,8 +322,11 @@ def _decode_tiles(p, M, K):
     """Dense W (16-bit patterns) back from the operand tiles of the dense-tile kernels, from the
     lane order the header documents: lane 16 g + n of a tile = row n of the stripe, columns
     4 g .. 4 g + 3 and 16 + 4 g .. of the tile's 32."""
-    _, _, T = p.layout(0, 0, 3)
+    _, _, T, occ = p.layout(0, 0, 3)
     nstripes, kt_pad = T.shape[:2]
+    bits = (occ[:, np.arange(kt_pad) // 32] >> (np.arange(kt_pad) % 32).astype(np.uint32)) & 1
+    assert np.array_equal(bits.astype(bool), T.reshape(nstripes, kt_pad, -1).any(axis=2))   # one bit per tile that keeps a weight
+    assert int(bits.sum()) == p.info(10)
     assert nstripes == (M + 15) // 16 and kt_pad * 32 >= K
     Wd = np.zeros((nstripes * 16, kt_pad * 32), dtype=np.uint16)
     for g in range(4):
@@ -329,16 +373,19 @@ def test_operand_tiles_are_not_built_for_large_matrices_or_fp32():
 
 @pytest.mark.parametrize("cfg", [c for c in CONFIGS if c.dtype != "f32"], ids=lambda c: c.name)
 def test_benchmark_layer_layouts_decode_to_the_dense_matrix(cfg):
-    """The layouts the benchmark layers actually run with (and the block-native alternative)."""
+    """The layouts the benchmark layers actually run with (and the block layout for all of them)."""
     from synthetic import make_layer
     blocks, W, _ = make_layer(cfg, N=16)
     dense_bits = W.view(np.uint16).copy()
     dense_bits[oracle.densify(np.ones((cfg.M, cfg.K)), cfg.bh, cfg.bw, blocks) == 0] = 0
     p = ubp.pack(W, cfg.dtype, cfg.bh, cfg.bw, blocks, device=ubp.HOST_ONLY)
     G = 4 if cfg.bh >= 16 else 2 if cfg.bh >= 8 else 1
-    for g, ct, native in [(G, 8, 1), (G, 2, 1), (max(G, 2), 8, 2)]:
-        Wd, _ = _decode_layout(p, g, ct, native, cfg.M, cfg.K, cfg.bh)
-        assert np.array_equal(Wd, dense_bits), (g, ct, native)
+    for g, ct in [(G, 8), (G, 2)]:
+        Wd, _ = _decode_layout(p, g, ct, cfg.M, cfg.K)
+        assert np.array_equal(Wd, dense_bits), (g, ct)
+    for G in (4, 5):
+        Wd, _ = _decode_block_layout(p, G, cfg.M, cfg.K)
+        assert np.array_equal(Wd, dense_bits)
     if cfg.name != "c4":                                 # (c4's zero-filled matrix would be 32 MB: not built)
         assert np.array_equal(_decode_tiles(p, cfg.M, cfg.K)[0], dense_bits)
     p.free()

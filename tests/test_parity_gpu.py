@@ -1,6 +1,7 @@
 """GPU parity: the HIP path, called through the C ABI, against the CPU oracle, element by
 element on the same seeded inputs."""
 import itertools
+import os
 
 import numpy as np
 import pytest
@@ -84,22 +85,6 @@ def test_stripe_kernel_small(shape, dtype):
             continue  # the staged tile does not hold all of K: the number of workgroup rows is not free
         Y = run_spmm(W, dtype, bh, bw, blocks, X, dtype, plan)
         check(Y, Yref, Yabs, dtype)
-    # block-native weight layout: whole blocks per step, one operand shared by the stripes
-    eligible = bh <= 16 and bw in (4, 8, 16, 32)
-    for G, CT in itertools.product((2, 4), (2, 4, 8)):
-        plan = _plan(kernel=2, sub_stripes=G, col_tiles=CT, native=2)
-        if not eligible:
-            with pytest.raises(ubp.UBPError):
-                run_spmm(W, dtype, bh, bw, blocks, X, dtype, plan)
-            continue
-        for y_dtype in (dtype, "f32"):
-            Y = run_spmm(W, dtype, bh, bw, blocks, X, y_dtype, plan)
-            check(Y, Yref, Yabs, dtype, y_dtype)
-    if eligible:
-        Y = run_spmm(W, dtype, bh, bw, blocks, X, dtype,
-                     _plan(kernel=2, sub_stripes=2, col_tiles=4, native=2, producers=2, waves=5))
-        check(Y, Yref, Yabs, dtype)
-
 
 TILE_SHAPES = [(64, 64, 200, 4, 4, 0.5), (100, 200, 336, 8, 8, 0.2), (130, 256, 1000, 16, 16, 0.15), (33, 40, 136, 5, 3, 0.3),
                (257, 31, 40, 1, 1, 0.3), (90, 64, 56, 20, 3, 0.25), (16, 16, 16, 16, 16, 1.0), (1040, 160, 520, 4, 4, 0.3),
@@ -108,23 +93,8 @@ TILE_SHAPES = [(64, 64, 200, 4, 4, 0.5), (100, 200, 336, 8, 8, 0.2), (130, 256, 
 
 @pytest.mark.parametrize("shape", TILE_SHAPES, ids=lambda s: "x".join(map(str, s)))
 @pytest.mark.parametrize("dtype", ["f16", "bf16"])
-def test_tile_kernel_small_k(shape, dtype):
-    """The output-stationary small-K kernel (W as zero-filled operand tiles in LDS, X staged
-    through LDS 32 rows at a time) in every tile shape, workgroup size and slice count,
-    including slices that end in a partial stripe and pixel blocks that hang over the right edge."""
-    M, K, N, bh, bw, d = shape
-    blocks, W, X = _layer(M, K, N, bh, bw, d, dtype, seed=M + K + 3)
-    Yref, Yabs = _oracle(W, dtype, bh, bw, blocks, X)
-    for CT, waves, slices in [(4, 0, 0), (2, 0, 0), (4, 1, 1), (2, 8, 3), (4, 8, 2), (2, 2, 100), (4, 4, 7), (2, 1, 2)]:
-        for y_dtype in (dtype, "f32"):
-            Y = run_spmm(W, dtype, bh, bw, blocks, X, y_dtype, _plan(kernel=3, col_tiles=CT, waves=waves, wg_rows=slices))
-            check(Y, Yref, Yabs, dtype, y_dtype)
-
-
-@pytest.mark.parametrize("shape", TILE_SHAPES, ids=lambda s: "x".join(map(str, s)))
-@pytest.mark.parametrize("dtype", ["f16", "bf16"])
 def test_x_stationary_kernel_small_k(shape, dtype):
-    """The other small-K kernel (X of a pixel block held in registers as operands, stripes of
+    """The small-K kernel (X of a pixel block held in registers as operands, stripes of
     W streamed past it, 16 finished rows stored at a time) in both tile widths, every
     workgroup size and several slice counts: more wavefronts than stripes, an odd number of
     stripes per wavefront, a pixel block that hangs over the right edge, a last stripe that
@@ -167,10 +137,10 @@ def test_chunked_x_stationary_kernel(shape, dtype):
 
 @pytest.mark.parametrize("dtype", ["f16", "bf16"])
 def test_dense_tile_kernels_with_padded_pitches(dtype):
-    """Kernels 3 to 5 on X and Y whose rows are longer than N (pitches that keep the rows 16-byte
+    """Kernels 4 and 5 on X and Y whose rows are longer than N (pitches that keep the rows 16-byte
     aligned, as these kernels require): nothing may be read as data or written beyond column N,
     and a ragged last pixel block must not spill into the padding."""
-    for M, K, N, bh, bw, d, kernels in [(100, 200, 200, 8, 8, 0.25, (3, 4)), (70, 256, 72, 4, 4, 0.3, (3, 4, 5)),
+    for M, K, N, bh, bw, d, kernels in [(100, 200, 200, 8, 8, 0.25, (4,)), (70, 256, 72, 4, 4, 0.3, (4, 5)),
                                         (150, 700, 136, 4, 4, 0.25, (5,))]:
         blocks, W, X = _layer(M, K, N, bh, bw, d, dtype, seed=M + K + 6)
         Yref, Yabs = _oracle(W, dtype, bh, bw, blocks, X)
@@ -185,25 +155,77 @@ def test_dense_tile_kernels_with_padded_pitches(dtype):
         check(run_spmm(W, dtype, bh, bw, blocks, X, dtype, None, ldx=N + 4, ldy=N + 2), Yref, Yabs, dtype)
 
 
-def test_automatic_kernel_choice_for_large_k():
-    """What ubp_spmm picks by itself must be the documented kernel's result bit for bit: the
-    chunked dense-tile kernel when K > 256 and at least a fifth of W is kept, gathered rows
-    otherwise - with block-native records for 16-row blocks on a K that does not fit the ring."""
+def test_automatic_kernel_choice():
+    """What ubp_spmm picks by itself must be the documented kernel's result bit for bit: dense
+    tiles (small-K or chunked kernel) while at least half the 16 x 32 tiles of W keep a weight,
+    gathered rows otherwise, and whole blocks as operands for 16-row blocks on a K beyond the ring."""
     M, K, N, bh, bw = 160, 1100, 256, 4, 4
     blocks, W, X = _layer(M, K, N, bh, bw, 0.25, "bf16", seed=91)
     Ya = run_spmm(W, "bf16", bh, bw, blocks, X, "f32")
     assert np.array_equal(Ya, run_spmm(W, "bf16", bh, bw, blocks, X, "f32", _plan(kernel=5)))
-    blocks, W, X = _layer(M, K, N, bh, bw, 0.1, "bf16", seed=92)          # too sparse for dense tiles
+    blocks, W, X = _layer(M, K, N, bh, bw, 0.01, "bf16", seed=92)         # most tiles empty: gathered rows
     Ya = run_spmm(W, "bf16", bh, bw, blocks, X, "f32")
     assert np.array_equal(Ya, run_spmm(W, "bf16", bh, bw, blocks, X, "f32", _plan(kernel=2)))
+    blocks, W, X = _layer(M, 160, N, bh, bw, 0.3, "f16", seed=94)
+    Ya = run_spmm(W, "f16", bh, bw, blocks, X, "f32")
+    assert np.array_equal(Ya, run_spmm(W, "f16", bh, bw, blocks, X, "f32", _plan(kernel=4)))
+    blocks, W, X = _layer(M, 160, N, bh, bw, 0.01, "f16", seed=95)
+    Ya = run_spmm(W, "f16", bh, bw, blocks, X, "f32")
+    assert np.array_equal(Ya, run_spmm(W, "f16", bh, bw, blocks, X, "f32", _plan(kernel=2)))
     M, K, N, bh, bw = 256, 4608, 2048, 16, 16                             # 72 chunks of X against a ring of 16
     blocks, W, X = _layer(M, K, N, bh, bw, 0.1, "bf16", seed=93)
     Yref, Yabs = _oracle(W, "bf16", bh, bw, blocks, X)
     Ya = run_spmm(W, "bf16", bh, bw, blocks, X, "f32")
     check(Ya, Yref, Yabs, "bf16", "f32")
-    Yn = run_spmm(W, "bf16", bh, bw, blocks, X, "f32", _plan(kernel=2, sub_stripes=4, col_tiles=4, native=2))
+    Yn = run_spmm(W, "bf16", bh, bw, blocks, X, "f32", _plan(kernel=6))
     assert np.array_equal(Ya, Yn)
     check(run_spmm(W, "bf16", bh, bw, blocks, X, "bf16"), Yref, Yabs, "bf16")   # 16-bit tiles leave through LDS rows
+
+
+BLOCK_SHAPES = [(130, 600, 1000, 16, 16, 0.15), (100, 300, 328, 8, 8, 0.2), (96, 700, 256, 4, 4, 0.25), (33, 40, 136, 5, 3, 0.3),
+                (70, 45, 72, 3, 1, 0.4), (16, 16, 64, 16, 16, 1.0), (257, 31, 104, 1, 1, 0.3), (300, 2500, 192, 16, 32, 0.1),
+                (150, 1300, 136, 16, 40, 0.2), (200, 3000, 64, 12, 16, 0.1), (64, 16, 200, 16, 16, 0.25)]
+
+
+@pytest.mark.parametrize("shape", BLOCK_SHAPES, ids=lambda s: "x".join(map(str, s)))
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+def test_block_kernel(shape, dtype):
+    """Whole blocks as operands (kernel 6): blocks of 16 rows and fewer, widths below, at and
+    above 16 and not a multiple of it, K below and beyond the ring, a ragged last column tile
+    (which the gather kernel serves), one or several producers, few and many consumers."""
+    M, K, N, bh, bw, d = shape
+    blocks, W, X = _layer(M, K, N, bh, bw, d, dtype, seed=M + K + 7)
+    Yref, Yabs = _oracle(W, dtype, bh, bw, blocks, X)
+    for G in (2, 4, 5):
+        for y_dtype in (dtype, "f32"):
+            Y = run_spmm(W, dtype, bh, bw, blocks, X, y_dtype, _plan(kernel=6, sub_stripes=G))
+            check(Y, Yref, Yabs, dtype, y_dtype)
+    for G, waves, NP in [(4, 3, 1), (2, 16, 4), (5, 5, 2), (2, 2, 1), (4, 16, 1), (5, 16, 2)]:
+        Y = run_spmm(W, dtype, bh, bw, blocks, X, dtype, _plan(kernel=6, sub_stripes=G, waves=waves, producers=NP))
+        check(Y, Yref, Yabs, dtype)
+
+
+def test_block_kernel_refuses_what_it_cannot_do():
+    blocks, W, X = _layer(90, 64, 128, 20, 3, 0.25, "bf16", seed=5)      # blocks taller than a stripe
+    with pytest.raises(ubp.UBPError):
+        run_spmm(W, "bf16", 20, 3, blocks, X, "bf16", _plan(kernel=6))
+    blocks, W, X = _layer(64, 12, 128, 4, 4, 0.3, "bf16", seed=6)        # K below one window
+    with pytest.raises(ubp.UBPError):
+        run_spmm(W, "bf16", 4, 4, blocks, X, "bf16", _plan(kernel=6))
+    blocks, W, X = _layer(64, 64, 48, 4, 4, 0.3, "bf16", seed=7)         # not one full column tile
+    with pytest.raises(ubp.UBPError):
+        run_spmm(W, "bf16", 4, 4, blocks, X, "bf16", _plan(kernel=6))
+    blocks, W, X = _layer(64, 64, 128, 4, 4, 0.3, "bf16", seed=8)
+    for bad in (dict(col_tiles=8), dict(sub_stripes=1), dict(sub_stripes=3), dict(waves=17), dict(producers=3)):
+        with pytest.raises(ubp.UBPError):
+            run_spmm(W, "bf16", 4, 4, blocks, X, "bf16", _plan(kernel=6, **bad))
+    with pytest.raises(ubp.UBPError):
+        run_spmm(W, "bf16", 4, 4, blocks, X, "bf16", _plan(kernel=6), ldx=132, ldy=128)   # rows not 16-byte aligned
+    blocks, W, X = _layer(64, 64, 128, 4, 4, 0.3, "f32", seed=9)
+    with pytest.raises(ubp.UBPError):
+        run_spmm(W, "f32", 4, 4, blocks, X, "f32", _plan(kernel=6))
+    with pytest.raises(ubp.UBPError):
+        run_spmm(W, "f32", 4, 4, blocks, X, "f32", _plan(kernel=3))       # there is no kernel 3
 
 
 def test_chunked_kernel_refuses_what_it_cannot_do():
@@ -222,8 +244,8 @@ def test_chunked_kernel_refuses_what_it_cannot_do():
         run_spmm(W, "f32", 4, 4, blocks, X, "f32", _plan(kernel=5))
 
 
-@pytest.mark.parametrize("kernel", [3, 4])
-def test_small_k_kernels_refuse_what_they_cannot_do(kernel):
+@pytest.mark.parametrize("kernel", [4])
+def test_small_k_kernel_refuses_what_it_cannot_do(kernel):
     blocks, W, X = _layer(64, 300, 64, 4, 4, 0.3, "bf16", seed=5)       # K too large
     with pytest.raises(ubp.UBPError):
         run_spmm(W, "bf16", 4, 4, blocks, X, "bf16", _plan(kernel=kernel))
@@ -273,15 +295,66 @@ def test_uneven_row_groups_share_the_lds_ring(dtype):
 
 
 # ------------------------------------------------------------------ exact special cases
-@pytest.mark.parametrize("dtype,kernel", [("f32", 1), ("f16", 1), ("bf16", 1), ("f16", 2), ("bf16", 2)])
-def test_identity_x_returns_densified_w_bit_exactly(dtype, kernel):
-    M, K, bh, bw = 90, 128, 4, 4
-    blocks = select_blocks(M, K, bh, bw, 0.3, seed=3)
+@pytest.mark.parametrize("dtype,kernel,K,bh,bw", [("f32", 1, 128, 4, 4), ("f16", 1, 128, 4, 4), ("bf16", 1, 128, 4, 4),
+                                                 ("f16", 2, 128, 4, 4), ("bf16", 2, 128, 4, 4), ("bf16", 2, 1280, 16, 16),
+                                                 ("f16", 4, 128, 4, 4), ("bf16", 4, 256, 8, 8),
+                                                 ("f16", 5, 512, 4, 4), ("bf16", 5, 512, 8, 8),
+                                                 ("f16", 6, 128, 4, 4), ("bf16", 6, 1280, 16, 16), ("bf16", 6, 512, 16, 32),
+                                                 ("bf16", 0, 1280, 16, 16), ("f16", 0, 128, 4, 4), ("bf16", 0, 512, 4, 4)])
+def test_identity_x_returns_densified_w_bit_exactly(dtype, kernel, K, bh, bw):
+    """X = I: every output is one kept weight times one, plus zeros - no rounding anywhere, so Y
+    must be the densified W bit for bit, through every kernel (0 = the automatic choice)."""
+    M = 90
+    blocks = select_blocks(M, K, bh, bw, 0.3 if bh < 16 else 0.15, seed=3)
     W = make_weights(M, K, 4, dtype)
     X = encode(np.eye(K, dtype=np.float32), dtype)
     Wd = oracle.densify(decode_f64(W, dtype), bh, bw, blocks)
-    Y = run_spmm(W, dtype, bh, bw, blocks, X, dtype, _plan(kernel=kernel))
-    assert np.array_equal(Y, Wd)
+    for y_dtype in {dtype, "f32"}:
+        Y = run_spmm(W, dtype, bh, bw, blocks, X, y_dtype, _plan(kernel=kernel))
+        assert np.array_equal(Y, Wd)
+
+
+@pytest.mark.parametrize("kernel", [1, 2, 4, 5, 6])
+def test_non_finite_x_reaches_only_what_the_header_says(kernel):
+    """An Inf and a NaN in two rows of X that no kept weight multiplies.  The vector kernel
+    multiplies kept weights only: Y is unaffected.  The MFMA kernels multiply zero-filled
+    operands: exactly the outputs the header names become NaN (in the two poisoned pixel
+    columns), all others are unaffected."""
+    M, K, N, bh, bw, dtype = 96, 256, 128, 16, 16, "bf16"
+    blocks = [(3, 40), (20, 200), (50, 130), (70, 232), (35, 80)]
+    W = make_weights(M, K, 11, dtype)
+    X = make_activations(K, N, 12, dtype, "normal")
+    Yclean, Yabs = _oracle(W, dtype, bh, bw, blocks, X)
+    Xp = X.copy()
+    k_inf, k_nan, px_inf, px_nan = 100, 150, 5, 77       # row 100: inside no block's columns; row 150: nor that one
+    Xp[k_inf, px_inf] = encode(np.array([np.inf], np.float32), dtype)[0]
+    Xp[k_nan, px_nan] = encode(np.array([np.nan], np.float32), dtype)[0]
+    Y = run_spmm(W, dtype, bh, bw, blocks, Xp, "f32", _plan(kernel=kernel), prefill=7.0)
+    bad = np.zeros((M, N), bool)
+    rows_of = lambda r0: np.arange(16 * (r0 // 16), 16 * (r0 // 16) + 16)          # noqa: E731
+    if kernel in (4, 5):
+        # rows of every stripe that keeps a weight within the aligned 32 rows of X around the poisoned row
+        for k, px in ((k_inf, px_inf), (k_nan, px_nan)):
+            for r, c in blocks:
+                if c < 32 * (k // 32) + 32 and c + bw > 32 * (k // 32):
+                    for rr in (r, r + bh - 1):
+                        bad[rows_of(rr)[rows_of(rr) < M], px] = True
+    elif kernel == 2:
+        pass        # no kept weight in those columns: the rows are never gathered
+    elif kernel == 6:
+        pass        # rows 100 and 150 lie in no block's 16-row window
+    assert np.isnan(Y[bad]).all() and np.isfinite(Y[~bad]).all()
+    assert np.abs(Y[~bad] - Yclean[~bad]).max() <= 2e-3 * np.abs(Yclean).max()
+    # poison INSIDE a window of the block kernel / a gathered row: the whole stripes that block reaches into
+    if kernel in (2, 6):
+        Xq = X.copy()
+        Xq[130 + 3, px_inf] = encode(np.array([np.inf], np.float32), dtype)[0]       # a column of block (50, 130)
+        Y = run_spmm(W, dtype, bh, bw, blocks, Xq, "f32", _plan(kernel=kernel), prefill=7.0)
+        rows = np.arange(50, 66)
+        assert not np.isfinite(Y[rows, px_inf]).all()                               # the exact sum holds it there
+        others = np.ones((M, N), bool)
+        others[:, px_inf] = False
+        assert np.isfinite(Y[others]).all()
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
@@ -331,14 +404,14 @@ def test_two_runs_are_bit_identical_and_columns_commute():
     assert np.array_equal(Y3, Y1[:, perm])
 
 
-@pytest.mark.parametrize("kernel", [2, 3, 4, 5])
+@pytest.mark.parametrize("kernel", [2, 4, 5, 6])
 def test_every_mfma_kernel_is_deterministic_and_column_order_free(kernel):
     """No kernel uses atomics on Y and every output element has one fixed summation order, whatever
     the pace of the wavefronts that hand data to each other: repeated runs agree bit for bit, and
     permuting the columns of X permutes the columns of Y."""
     M, K, N, bh, bw = 144, 512, 384, 8, 8
     blocks, W, X = _layer(M, K, N, bh, bw, 0.25, "bf16", seed=17)
-    if kernel in (3, 4):
+    if kernel == 4:
         K = 256
         blocks, W, X = _layer(M, K, N, bh, bw, 0.25, "bf16", seed=18)
     plan = _plan(kernel=kernel)
@@ -373,43 +446,52 @@ def test_device_errors_and_noop():
 
 
 # ------------------------------------------------------------------ the five layers at full size
-@pytest.mark.parametrize("name", ["c0", "c1", "c2"])
+_FULL = {}
+
+
+def _full_reference(name):
+    """The oracle over the whole layer (all rows, all columns), computed once per session.  The
+    oracle itself is one plain thread; the test hands it disjoint row ranges from several threads
+    (the C call releases the interpreter lock), which changes no value."""
+    if name not in _FULL:
+        from concurrent.futures import ThreadPoolExecutor
+        cfg = get_config(name)
+        blocks, W, X = make_layer(cfg)
+        W64, X64 = decode_f64(W, cfg.dtype), decode_f64(X, cfg.dtype)
+        want_abs = cfg.dtype == "f32"                      # the componentwise bound is the fp32 layer's
+        step = max(1, min(128, cfg.M // 16))
+        ranges = [np.arange(r, min(r + step, cfg.M)) for r in range(0, cfg.M, step)]
+        with ThreadPoolExecutor(max_workers=min(16, os.cpu_count() or 1)) as ex:
+            parts = list(ex.map(lambda rows: oracle.spmm(W64, cfg.bh, cfg.bw, blocks, X64, rows=rows, want_abs=want_abs), ranges))
+        if want_abs:
+            Yref, Yabs = np.concatenate([p[0] for p in parts]), np.concatenate([p[1] for p in parts])
+        else:
+            Yref, Yabs = np.concatenate(parts), None
+        _FULL[name] = (cfg, blocks, W, X, Yref, Yabs)
+    return _FULL[name]
+
+
+@pytest.mark.parametrize("name", ["c0", "c1", "c2", "c3", "c4"])
 def test_layer_full_oracle(name):
-    cfg = get_config(name)
-    blocks, W, X = make_layer(cfg)
-    Yref, Yabs = _oracle(W, cfg.dtype, cfg.bh, cfg.bw, blocks, X)
-    for y_dtype in {cfg.dtype, "f32"}:
+    """Every element of Y of the five layers at full size against the oracle, through what
+    ubp_spmm picks by itself (the launch shape the benchmark times), in both output types."""
+    cfg, blocks, W, X, Yref, Yabs = _full_reference(name)
+    for y_dtype in sorted({cfg.dtype, "f32"}):
         Y = run_spmm(W, cfg.dtype, cfg.bh, cfg.bw, blocks, X, y_dtype)
         check(Y, Yref, Yabs, cfg.dtype, y_dtype)
-    if cfg.dtype != "f32":
-        Y = run_spmm(W, cfg.dtype, cfg.bh, cfg.bw, blocks, X, cfg.dtype, _plan(kernel=1))
-        check(Y, Yref, Yabs, cfg.dtype)
 
 
-@pytest.mark.parametrize("name", ["c3", "c4"])
-def test_layer_full_size_sampled_rows(name):
-    """At full size the oracle computes a sample of output rows (all columns of each): the
-    first and last rows, rows around stripe boundaries, and a seeded random draw; max|Y| of
-    the sample scales the tolerance.  Every other element is checked to be finite and
-    consistent between the two kernels."""
-    cfg = get_config(name)
-    blocks, W, X = make_layer(cfg)
-    rng = np.random.default_rng(42)
-    rows = sorted(set([0, 1, 15, 16, 17, 31, 32, cfg.M - 17, cfg.M - 16, cfg.M - 1]) |
-                  set(int(r) for r in rng.integers(0, cfg.M, size=22)))
-    Yref, Yabs = _oracle(W, cfg.dtype, cfg.bh, cfg.bw, blocks, X, rows=rows)
-    Y = run_spmm(W, cfg.dtype, cfg.bh, cfg.bw, blocks, X, cfg.dtype)
-    check(Y[rows], Yref, Yabs, cfg.dtype)
-    Y32 = run_spmm(W, cfg.dtype, cfg.bh, cfg.bw, blocks, X, "f32")
-    check(Y32[rows], Yref, Yabs, cfg.dtype, "f32")
-    # the two kernels accumulate in different orders; both in fp32
-    Yv = run_spmm(W, cfg.dtype, cfg.bh, cfg.bw, blocks, X, "f32", _plan(kernel=1))
-    check(Yv[rows], Yref, Yabs, cfg.dtype, "f32")
-    assert np.abs(Yv - Y32).max() <= 1e-4 * np.abs(Yref).max()
-    for G, CT in [(1, 8), (2, 8), (4, 4), (2, 2)]:
-        Yp = run_spmm(W, cfg.dtype, cfg.bh, cfg.bw, blocks, X, "f32", _plan(kernel=2, sub_stripes=G, col_tiles=CT))
-        assert np.abs(Yv - Yp).max() <= 1e-4 * np.abs(Yref).max(), (G, CT)
-    for G, CT, NP in [(4, 8, 2), (2, 4, 1), (4, 2, 4)]:
-        Yp = run_spmm(W, cfg.dtype, cfg.bh, cfg.bw, blocks, X, "f32",
-                      _plan(kernel=2, sub_stripes=G, col_tiles=CT, native=2, producers=NP))
-        assert np.abs(Yv - Yp).max() <= 1e-4 * np.abs(Yref).max(), ("native", G, CT)
+@pytest.mark.parametrize("name", ["c1", "c2", "c3", "c4"])
+def test_layer_full_size_other_kernels(name):
+    """The kernels ubp_spmm does not pick for a layer, at full size, against the same full oracle."""
+    cfg, blocks, W, X, Yref, Yabs = _full_reference(name)
+    plans = [_plan(kernel=1), _plan(kernel=2)]
+    if name == "c4":
+        plans += [_plan(kernel=2, sub_stripes=4, col_tiles=8), _plan(kernel=6, sub_stripes=2), _plan(kernel=6, waves=10, producers=4)]
+    elif name == "c3":
+        plans += [_plan(kernel=2, sub_stripes=1, col_tiles=8), _plan(kernel=6)]
+    else:
+        plans += [_plan(kernel=6), _plan(kernel=4, col_tiles=2)]
+    for plan in plans:
+        Y = run_spmm(W, cfg.dtype, cfg.bh, cfg.bw, blocks, X, "f32", plan)
+        check(Y, Yref, Yabs, cfg.dtype, "f32")
