@@ -5,8 +5,14 @@ A step is one ubp_spmm call (the whole hot path: the packed weights times one ba
 synthetic activations) with all inputs already resident in HBM.  Steps rotate through
 enough distinct (X, Y, packed W) buffer sets that more than twice the 256 MB Infinity
 Cache is touched between two uses of a set ("cold"), so the time is an HBM time.  The K
-timed steps are recorded once into a HIP graph and replayed, which removes the host's
-launch cost from the measurement; HIP events on the launch stream bracket the replay.
+timed steps are recorded once into a HIP graph, which removes the host's launch cost from
+the measurement; the graph is replayed until at least 50 ms have been timed (the first
+milliseconds of a burst run at a lower clock), HIP events on the launch stream bracket every
+replay, and the per-launch kernel time is the median replay divided by K.
+
+After timing, every handle's error flags are read and the last Y of the headline layer is
+compared with the CPU oracle on a sample of rows: a kernel that produced wrong numbers makes
+the run fail instead of being reported.
 
 Prints ONE JSON line: the headline workload (default c4) plus, under "per_config", the
 same measurement for the other layers.  `value` counts flops on kept weights only
@@ -26,6 +32,8 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0            # MI355X HBM3E, published
 MFMA_PEAK_TFLOPS = 2500.0        # dense bf16 / fp16 MFMA, published
 INFINITY_CACHE_BYTES = 256 << 20
+MIN_TIMED_MS = 50.0
+KERNEL_NAMES = {1: "wros_kernel", 2: "stripe_kernel", 4: "xstat_kernel", 5: "xchunk_kernel", 6: "blk_kernel"}
 
 
 def algorithmic_bytes(cfg, nb, N, y_bytes):
@@ -35,22 +43,38 @@ def algorithmic_bytes(cfg, nb, N, y_bytes):
     return w + cfg.K * N * esz + cfg.M * N * y_bytes
 
 
-def measure(cfg_name, steps, warmup, y_dtype, plan_kw, use_graph, hot):
+def timed_replays(run_once, stream, est_ms):
+    """Replays until MIN_TIMED_MS are covered.  Returns (wall seconds of all replays, list of
+    per-replay event milliseconds)."""
+    import torch
+    reps = int(min(2000, max(3, np.ceil(MIN_TIMED_MS / max(est_ms, 1e-3)))))
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for e0, e1 in ev:
+        e0.record(stream)
+        run_once()
+        e1.record(stream)
+    stream.synchronize()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    return wall, [e0.elapsed_time(e1) for e0, e1 in ev]
+
+
+def measure(cfg, layer, steps, warmup, y_dtype, plan_kw, use_graph, hot, verify_rows=0):
     import torch
     import paper_2407_19644_amd as ubp
-    from synthetic import get_config, make_layer
 
-    cfg = get_config(cfg_name)
-    blocks, W, X = make_layer(cfg)
+    blocks, W, X = layer
     nb = len(blocks)
-    N = cfg.N
+    N = X.shape[1]
     y_dtype = y_dtype or cfg.dtype
     tdt = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}
     y_bytes = 4 if y_dtype == "f32" else 2
     abytes = algorithmic_bytes(cfg, nb, N, y_bytes)
-    set_bytes = abytes
-    nsets = 1 if hot else int(np.ceil(2.0 * INFINITY_CACHE_BYTES / set_bytes)) + 1
-    nsets = max(1, min(nsets, 192))
+    want_sets = int(np.ceil(2.0 * INFINITY_CACHE_BYTES / abytes)) + 1
+    nsets = 1 if hot else max(1, min(want_sets, steps, 192))   # a set no step touches would only cost memory
+    cold = (not hot) and nsets >= want_sets
 
     Xt = torch.from_numpy(X)
     if cfg.dtype == "bf16":
@@ -58,13 +82,16 @@ def measure(cfg_name, steps, warmup, y_dtype, plan_kw, use_graph, hot):
     Xs, Ys, Ps = [], [], []
     for s in range(nsets):
         Xs.append(Xt.cuda() if s == 0 else Xs[0].clone())
-        Ys.append(torch.empty((cfg.M, N), dtype=tdt[y_dtype], device="cuda"))
+        Ys.append(torch.full((cfg.M, N), float("nan"), dtype=tdt[y_dtype], device="cuda"))
         Ps.append(ubp.pack(W, cfg.dtype, cfg.bh, cfg.bw, blocks, device=0))
     plan = None
     if plan_kw:
         plan = ubp.Plan()
         for k, v in plan_kw.items():
             setattr(plan, k, v)
+    # everything a first call would allocate or build is done here, outside any timing or capture
+    for s in range(nsets):
+        chosen = ubp.spmm_prepare(Ps[s], Xs[s].data_ptr(), N, N, Ys[s].data_ptr(), N, y_dtype, plan)
 
     def step(i, stream):
         s = i % nsets
@@ -76,49 +103,90 @@ def measure(cfg_name, steps, warmup, y_dtype, plan_kw, use_graph, hot):
         for i in range(warmup):
             step(i, sp)
         stream.synchronize()
-        graph = None
         if use_graph:
             graph = torch.cuda.CUDAGraph()
             with torch.cuda.graph(graph, stream=stream):
                 for i in range(steps):
                     step(warmup + i, stream.cuda_stream)
-            graph.replay()                # one untimed replay (graph upload)
-            stream.synchronize()
-        e0 = torch.cuda.Event(enable_timing=True)
-        e1 = torch.cuda.Event(enable_timing=True)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        e0.record(stream)
-        if graph is not None:
-            graph.replay()
+            run_once = graph.replay
         else:
-            for i in range(steps):
-                step(warmup + i, sp)
+            def run_once():
+                for i in range(steps):
+                    step(warmup + i, sp)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        run_once()                        # one untimed replay (graph upload) that also sizes the timed region
         e1.record(stream)
         stream.synchronize()
-        torch.cuda.synchronize()
-        wall = time.perf_counter() - t0
-    ev_ms = e0.elapsed_time(e1)
-    ms_per_step = wall * 1e3 / steps
-    kernel_us = ev_ms * 1e3 / steps        # average launch duration inside the timed region
+        wall, ev_ms = timed_replays(run_once, stream, e0.elapsed_time(e1))
+    reps = len(ev_ms)
+    ms_per_step = wall * 1e3 / (reps * steps)
+    kernel_us = float(np.median(ev_ms)) * 1e3 / steps      # per launch, median replay
     flops = 2.0 * nb * cfg.bh * cfg.bw * N
     t_hbm = abytes / (HBM_PEAK_GBS * 1e9)
     t_mfma = flops / (MFMA_PEAK_TFLOPS * 1e12) if cfg.dtype != "f32" else 0.0
+
+    flags = [p.device_error() for p in Ps]
+    if any(flags):
+        raise RuntimeError("%s: a bounded wait inside a kernel ran out (flags %s): the timing is void" % (cfg.name, flags))
+    checked = 0
+    if verify_rows:
+        checked = verify(cfg, layer, Ys[(warmup + steps - 1) % nsets], y_dtype, verify_rows)
+
+    issued = {2: 100 + ubp.layout_slot(chosen.sub_stripes, chosen.col_tiles) if chosen.kernel == 2 else -1,
+              4: 10, 5: 10, 6: 300 + {2: 0, 4: 1, 5: 2}.get(chosen.sub_stripes, 1)}.get(chosen.kernel, -1)
     res = {
         "workload": cfg.name, "what": cfg.what, "M": cfg.M, "K": cfg.K, "N": N, "block": "%dx%d" % (cfg.bh, cfg.bw),
         "density": cfg.density, "nb": nb, "in_dtype": cfg.dtype, "y_dtype": y_dtype,
         "gflops_kept": flops / (ms_per_step * 1e-3) / 1e9,
-        "ms_per_step": ms_per_step, "kernel_us": kernel_us,
+        "ms_per_step": ms_per_step, "kernel_us": kernel_us, "kernel_us_min": float(min(ev_ms)) * 1e3 / steps,
         "algorithmic_bytes": abytes, "achieved_GBs": abytes / (kernel_us * 1e-6) / 1e9,
         "hbm_frac": (abytes / (kernel_us * 1e-6) / 1e9) / HBM_PEAK_GBS,
-        "t_roof_us": max(t_hbm, t_mfma) * 1e6, "cache": "hot" if hot else "cold", "buffer_sets": nsets,
-        "graph": bool(use_graph),
+        "t_roof_us": max(t_hbm, t_mfma) * 1e6, "cache": "cold" if cold else ("hot" if hot else "warm"), "buffer_sets": nsets,
+        "graph": bool(use_graph), "replays": reps,
+        "kernel": KERNEL_NAMES.get(chosen.kernel, "?"),
+        "shape": {"sub_stripes": chosen.sub_stripes, "col_tiles": chosen.col_tiles, "waves": chosen.waves,
+                  "producers": chosen.producers, "wg_rows": chosen.wg_rows},
+        "mfma_needed": Ps[0].info(9) if cfg.dtype != "f32" else None,
+        "mfma_issued": Ps[0].info(issued) if issued >= 0 else None,
+        "device_bytes_per_handle": Ps[0].info(8), "canonical_bytes": Ps[0].info(7),
+        "rows_checked_against_oracle": checked,
     }
     for p in Ps:
         p.free()
     del Xs, Ys
     torch.cuda.empty_cache()
-    return res, (cfg, blocks, W, X)
+    return res
+
+
+def verify(cfg, layer, Yt, y_dtype, nrows):
+    """Rows of the timed run's last Y against the oracle (first, last, stripe borders and a seeded
+    draw); raises on a mismatch.  Tolerances as in the parity tests."""
+    import torch
+    import oracle
+    from synthetic import decode_f64
+    blocks, W, X = layer
+    rng = np.random.default_rng(7)
+    rows = sorted(set([0, 15, 16, cfg.M - 16, cfg.M - 1]) | set(int(r) for r in rng.integers(0, cfg.M, size=max(0, nrows - 5))))
+    Yref = oracle.spmm(decode_f64(W, cfg.dtype), cfg.bh, cfg.bw, blocks, decode_f64(X, cfg.dtype), rows=rows)
+    t = Yt[torch.tensor(rows, device=Yt.device)].detach().cpu()
+    Y = decode_f64(t.view(torch.uint16).numpy(), "bf16") if y_dtype == "bf16" else t.numpy().astype(np.float64)
+    if not np.isfinite(Y).all():
+        raise RuntimeError("%s: Y holds NaN/Inf after the timed run" % cfg.name)
+    scale = np.abs(Yref).max()
+    err = np.abs(Y - Yref)
+    if cfg.dtype == "f32":
+        ok = err.max() <= 1e-5 * scale
+    elif y_dtype == "f32":
+        ok = err.max() <= 2e-3 * scale
+    else:
+        mant, emin = (10, -24) if y_dtype == "f16" else (7, -133)
+        a = np.maximum(np.abs(Yref), 2.0 ** (emin + mant))
+        half_ulp = 0.5 * np.maximum(2.0 ** (np.floor(np.log2(a)) - mant), 2.0 ** emin)
+        ok = bool((err <= 1.01 * half_ulp + 1e-4 * scale).all())
+    if not ok:
+        raise RuntimeError("%s: the timed run's Y does not match the oracle (max err %.3e, max |Y| %.3e)" % (cfg.name, err.max(), scale))
+    return len(rows)
 
 
 def cpu_baseline(cfg, blocks, W, X, budget_s=15.0):
@@ -144,22 +212,49 @@ def cpu_baseline(cfg, blocks, W, X, budget_s=15.0):
                       % (R, cfg.M, cfg.N, dt, 2.0 * R * cfg.K * cfg.N / dt / 1e9)}
 
 
-def kernel_name(cfg, pinned):
-    """The kernel ubp_spmm runs for this layer (same rule as the library's), or the pinned one."""
-    if cfg.dtype == "f32" or pinned == 1:
-        return "wros_kernel"
-    if pinned == 3:
-        return "tile_kernel"
-    if pinned == 4 or (pinned == 0 and cfg.K <= 256 and cfg.N % 8 == 0):
-        return "xstat_kernel"
-    tiles_mb = ((cfg.M + 15) // 16) * 8 * ((cfg.K + 255) // 256) / 1024.0   # zero-filled W as operand tiles
-    if pinned == 5 or (pinned == 0 and cfg.N % 8 == 0 and tiles_mb <= 8 and cfg.density >= 0.2):
-        return "xchunk_kernel"
-    return "stripe_kernel"
+def launch_floor_us():
+    """Per-launch time of an empty kernel, graph-replayed like the layers: what no layer can beat."""
+    import torch
+    import paper_2407_19644_amd as ubp
+    stream = torch.cuda.Stream()
+    n = 200
+    with torch.cuda.stream(stream):
+        for _ in range(10):
+            ubp.launch_floor(stream.cuda_stream)
+        stream.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=stream):
+            for _ in range(n):
+                ubp.launch_floor(stream.cuda_stream)
+        graph.replay()
+        stream.synchronize()
+        _, ev = timed_replays(graph.replay, stream, 1.0)
+    return float(np.median(ev)) * 1e3 / n
+
+
+def copy_bandwidth_GBs():
+    """Bytes read plus bytes written per second of a plain device copy, on rotating buffers larger
+    than the Infinity Cache: what a kernel with no arithmetic gets out of this box's memory."""
+    import torch
+    stream = torch.cuda.Stream()
+    n = 256 << 20
+    bufs = [torch.empty(n, dtype=torch.uint8, device="cuda") for _ in range(4)]
+    with torch.cuda.stream(stream):
+        for b in bufs:
+            b.zero_()
+        stream.synchronize()
+
+        def once():
+            for i in range(4):
+                bufs[(i + 1) % 4].copy_(bufs[i])
+        once()
+        stream.synchronize()
+        _, ev = timed_replays(once, stream, 1.0)
+    return 4 * 2.0 * n / (float(np.median(ev)) * 1e-3) / 1e9
 
 
 def load_traffic(workload, y_dtype):
-    """HBM bytes per launch from the committed rocprofv3 --pmc summaries, if present."""
+    """HBM bytes per launch from the committed rocprofv3 --pmc summaries (profiles/traffic.json), if present."""
     path = os.path.join(ROOT, "profiles", "traffic.json")
     try:
         with open(path) as f:
@@ -174,7 +269,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--config", default="c4", help="headline workload (c0..c4)")
+    ap.add_argument("--config", default="c4", help="headline workload (a name from synthetic/configs.py)")
     ap.add_argument("--y-dtype", default=None, help="f32, or the layer's input dtype (default)")
     ap.add_argument("--only", action="store_true", help="skip the per_config table of the other layers")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
@@ -197,6 +292,7 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
     import paper_2407_19644_amd as ubp
+    from synthetic import CONFIGS, EXTRA_CONFIGS, aligned_twin, get_config, make_layer
     ubp.load_library()                      # fails loudly if the native library is missing
     plan_kw = {k: v for k, v in (("kernel", args.kernel), ("sub_stripes", args.G), ("col_tiles", args.CT),
                                  ("waves", args.waves)) if v}
@@ -208,18 +304,37 @@ def main():
             torch.add(src, 1.0, out=dst)
         torch.cuda.synchronize()
         del src, dst
-    head, data = measure(args.config, args.steps, args.warmup, args.y_dtype, plan_kw, use_graph, args.hot)
+    cfg = get_config(args.config)
+    layer = make_layer(cfg)
+    head = measure(cfg, layer, args.steps, args.warmup, args.y_dtype, plan_kw, use_graph, args.hot, verify_rows=32)
     per = {}
+    keys = ("gflops_kept", "kernel_us", "achieved_GBs", "hbm_frac", "t_roof_us", "algorithmic_bytes", "kernel", "cache",
+            "mfma_needed", "mfma_issued")
     if not args.only:
-        for name in ("c1", "c2", "c3", "c4"):
+        for c in CONFIGS[1:]:
             for yd in (None, "f32"):
-                if name == args.config and (yd or None) == (args.y_dtype or None):
+                if c.name == cfg.name and (yd or None) == (args.y_dtype or None):
                     r = head
                 else:
-                    r, _ = measure(name, args.steps, args.warmup, yd, plan_kw, use_graph, args.hot)
-                per["%s/y_%s" % (name, r["y_dtype"])] = {k: r[k] for k in (
-                    "gflops_kept", "kernel_us", "achieved_GBs", "hbm_frac", "t_roof_us", "algorithmic_bytes")}
-    cfg = data[0]
+                    lay = layer if c.name == cfg.name else make_layer(c)
+                    want = int(np.ceil(2.0 * INFINITY_CACHE_BYTES / algorithmic_bytes(c, len(lay[0]), c.N, 4 if yd else 2))) + 1
+                    # (small layers: enough steps per replay to rotate through a cold number of sets)
+                    r = measure(c, lay, max(args.steps, min(want, 192)), args.warmup, yd, plan_kw, use_graph, args.hot,
+                                verify_rows=8)
+                per["%s/y_%s" % (c.name, r["y_dtype"])] = {k: r[k] for k in keys}
+        # the paper's own block shapes (N x 1 and N x (h w)) on MobileNetV1-shaped layers: unaligned
+        # (UBP) beside the same number of blocks at aligned origins (ABP), as in the paper's Fig. 6
+        for c in EXTRA_CONFIGS:
+            lay = make_layer(c)
+            want = int(np.ceil(2.0 * INFINITY_CACHE_BYTES / algorithmic_bytes(c, len(lay[0]), c.N, 2))) + 1
+            st = max(args.steps, min(want, 192))
+            r = measure(c, lay, st, args.warmup, None, plan_kw, use_graph, args.hot, verify_rows=8)
+            ca = aligned_twin(c)
+            ra = measure(ca, make_layer(ca), st, args.warmup, None, plan_kw, use_graph, args.hot, verify_rows=8)
+            e = {k: r[k] for k in keys}
+            e.update({"abp_kernel_us": ra["kernel_us"], "abp_kernel": ra["kernel"], "ubp_over_abp": r["kernel_us"] / ra["kernel_us"],
+                      "block": r["block"], "density": c.density})
+            per["%s/y_%s" % (c.name, r["y_dtype"])] = e
     out = {
         "metric": "UBP SpMM effective GFLOP/s (kept-weight FLOPs) + % of HBM/MFMA roofline",
         "value": head["gflops_kept"], "unit": "GFLOP/s",
@@ -228,15 +343,20 @@ def main():
         "dtype": cfg.dtype,          # multiplications in this type on the matrix cores, sums in f32
         "data": "synthetic",
         "config": {k: head[k] for k in ("workload", "what", "M", "K", "N", "block", "density", "nb", "in_dtype",
-                                        "y_dtype", "cache", "buffer_sets", "graph")},
+                                        "y_dtype", "cache", "buffer_sets", "graph", "replays", "shape",
+                                        "rows_checked_against_oracle", "device_bytes_per_handle", "canonical_bytes")},
         "roofline": {"bound": "hbm", "achieved": head["achieved_GBs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": head["hbm_frac"], "traffic": load_traffic(head["workload"], head["y_dtype"]),
-                     "kernel": kernel_name(cfg, args.kernel),
-                     "kernel_us": head["kernel_us"], "algorithmic_bytes": head["algorithmic_bytes"],
-                     "t_roof_us": head["t_roof_us"]},
+                     "traffic_source": "profiles/traffic.json (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a copy kernel)",
+                     "kernel": head["kernel"],
+                     "kernel_us": head["kernel_us"], "kernel_us_min": head["kernel_us_min"],
+                     "algorithmic_bytes": head["algorithmic_bytes"], "t_roof_us": head["t_roof_us"],
+                     "mfma_needed": head["mfma_needed"], "mfma_issued": head["mfma_issued"],
+                     "launch_floor_us": launch_floor_us(), "copy_GBs": copy_bandwidth_GBs()},
     }
+    out["roofline"]["frac_of_copy"] = head["achieved_GBs"] / out["roofline"]["copy_GBs"]
     if not args.no_cpu:
-        out["cpu_baseline"] = cpu_baseline(*data)
+        out["cpu_baseline"] = cpu_baseline(cfg, *layer)
     if per:
         out["per_config"] = per
     print(json.dumps(out))

@@ -17,7 +17,7 @@ class LayerConfig:
     bw: int           # block width (consecutive input channels)
     density: float    # kept fraction of W's elements (1 - pruning rate)
     dtype: str        # "f32" | "f16" | "bf16"  (input element type)
-    mask_mode: str    # "uniform" | "zipf"
+    mask_mode: str    # "uniform" | "zipf" | "col_aligned" | "aligned"
     zipf_s: float     # Zipf exponent over bh-row stripes (zipf mode only)
     x_dist: str       # "uniform01" | "relu_normal" | "normal"
     mask_seed: int
@@ -40,8 +40,32 @@ CONFIGS = (
 )
 
 
+# The paper's own block shapes on MobileNetV1-shaped layers (Section 3.1, Section 5.4): N consecutive
+# output channels x one input channel for pointwise convolutions (N = 2, 4, 8 at 70 / 80 / 90 %
+# sparsity), and N x (3 x 3) with column origins on multiples of 9 for a 3 x 3 convolution lowered
+# to a matrix.  Batch 32.
+EXTRA_CONFIGS = (
+    LayerConfig("n1", 256, 256, 25088, 2, 1, 0.30, "f16", "uniform", 0.0, "relu_normal",
+                1011, 2011, 3011, "MobileNetV1 pointwise 256->256 at 28x28, 2x1 blocks, 70 % sparsity"),
+    LayerConfig("n2", 512, 512, 6272, 4, 1, 0.20, "f16", "uniform", 0.0, "relu_normal",
+                1012, 2012, 3012, "MobileNetV1 pointwise 512->512 at 14x14, 4x1 blocks, 80 % sparsity"),
+    LayerConfig("n3", 1024, 1024, 1568, 8, 1, 0.10, "f16", "uniform", 0.0, "relu_normal",
+                1013, 2013, 3013, "MobileNetV1 pointwise 1024->1024 at 7x7, 8x1 blocks, 90 % sparsity"),
+    LayerConfig("n4", 256, 2304, 6272, 4, 9, 0.20, "bf16", "col_aligned", 0.0, "relu_normal",
+                1014, 2014, 3014, "3x3 convolution 256->256 at 14x14 via im2col, 4x(3x3) blocks, 80 % sparsity"),
+)
+
+
+def aligned_twin(cfg: LayerConfig) -> LayerConfig:
+    """The same layer with the same number of blocks at ALIGNED origins (aligned block pruning)."""
+    from dataclasses import replace
+    return replace(cfg, name=cfg.name + "_abp", mask_mode="aligned", what=cfg.what + " (aligned origins)")
+
+
 def get_config(name: str) -> LayerConfig:
-    for c in CONFIGS:
+    for c in CONFIGS + EXTRA_CONFIGS:
         if c.name == name:
             return c
+        if c.name + "_abp" == name:
+            return aligned_twin(c)
     raise KeyError(name)

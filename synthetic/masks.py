@@ -21,6 +21,11 @@ lists bit for bit:
   stripes by a Fisher-Yates shuffle driven by the same RNG (before any sampling); then
   stripe by stripe, r = bh * stripe + bounded(rows in stripe), c = bounded(K - bw + 1),
   accept iff free.
+* "col_aligned": as "uniform" with c = bw * bounded(K // bw): the paper's convolution block
+  (N, 1, h, w), which in the lowered matrix is N x (h w) with a column origin that is a multiple
+  of h w (Section 3.1); rows stay unaligned.
+* "aligned": r = bh * bounded(M // bh), c = bw * bounded(K // bw): aligned block pruning, the
+  special case the paper compares against (Section 3.1, Section 5.4).
 * the result is sorted by (r, c).
 """
 import math
@@ -102,15 +107,15 @@ def select_blocks(M, K, bh, bw, density, seed, mode="uniform", zipf_s=0.0):
     nr, nc = M - bh + 1, K - bw + 1
     max_attempts = 2000 * nb + 100000
 
-    def fill(count, r_base, r_span):
+    def fill(count, r_base, r_span, r_unit=1, c_unit=1):
         attempts = 0
         got = 0
         while got < count:
             attempts += 1
             if attempts > max_attempts:
                 raise RuntimeError("infeasible: rejection sampling did not terminate")
-            r = r_base + rng.bounded(r_span)
-            c = rng.bounded(nc)
+            r = r_base + r_unit * rng.bounded(r_span)
+            c = c_unit * rng.bounded(nc if c_unit == 1 else K // bw)
             cell = occ[r:r + bh, c:c + bw]
             if cell.any():
                 continue
@@ -120,6 +125,12 @@ def select_blocks(M, K, bh, bw, density, seed, mode="uniform", zipf_s=0.0):
 
     if mode == "uniform":
         fill(nb, 0, nr)
+    elif mode == "col_aligned":
+        fill(nb, 0, nr, 1, bw)
+    elif mode == "aligned":
+        if nb > (M // bh) * (K // bw):
+            raise ValueError("infeasible: more blocks than aligned positions")
+        fill(nb, 0, M // bh, bh, bw)
     elif mode == "zipf":
         S = (nr + bh - 1) // bh
         cap = int(math.floor(0.375 * float(K) / float(bw)))
