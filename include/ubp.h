@@ -127,7 +127,7 @@ const void *ubp_packed_values(const ubp_packed *p, int64_t *len_elems);
  * UBP_ERR_ALLOC, UBP_ERR_DEVICE (launch failed).  Nothing is written to Y on error.
  * Non-finite X: the MFMA kernels multiply whole operand tiles, zero weights included.  An Inf
  * or NaN in a row of X therefore reaches (as NaN) outputs whose exact sum does not contain it:
- * with kernels 4 and 5, every output row whose 16-row stripe keeps a weight within the aligned
+ * with kernels 4, 5 and 7, every output row whose 16-row stripe keeps a weight within the aligned
  * 32 rows of X around it; with kernel 2, every row of a row group that keeps a weight in that
  * column; with kernel 6, every row of a stripe that a block reaches into whose 16-row window of X
  * (its columns, moved left at the right edge) contains it.  Kernel 1 multiplies kept weights only.
@@ -142,8 +142,8 @@ ubp_status ubp_spmm(const ubp_packed *p, const void *X_dev, int64_t ldx, int32_t
  *                dtype, bh <= 16).
  *                2 = MFMA kernel on aligned 16-row stripes that gathers the rows of X a row
  *                group needs (f16 / bf16).
- *                4 and 5 = MFMA kernels that use W as zero-filled 16 x 32 operand tiles, skipping
- *                tiles that keep nothing (f16 / bf16, N a multiple of 8, 16-byte
+ *                4, 5 and 7 = MFMA kernels that use W as zero-filled 16 x 32 operand tiles; 4 and 5
+ *                skip tiles that keep nothing (f16 / bf16, N a multiple of 8, 16-byte
  *                aligned rows of X and Y; col_tiles 2 or 4; wg_rows = slices the stripes are
  *                cut into, one workgroup per slice and pixel block).
  *                4 (K <= 256) keeps the X of one pixel block in registers and streams the stripes
@@ -155,13 +155,21 @@ ubp_status ubp_spmm(const ubp_packed *p, const void *X_dev, int64_t ldx, int32_t
  *                6 = MFMA kernel with whole blocks as operands, stored by row modulo 16 - the
  *                paper's rotation with period 16 (f16 / bf16, bh <= 16, 16 <= K < 65408, N >= 64,
  *                16-byte aligned rows; col_tiles 4 only; sub_stripes 2, 4 or 5).
- *                0 picks 1 for fp32; 6 for 16-row blocks at least 16 wide when K > 1024; else 4
- *                (K <= 256) or 5 when at least half of the 16 x 32 tiles of W keep a weight; else 2.
+ *                7 = MFMA kernel on the same operand tiles with BOTH operands staged in LDS: a
+ *                workgroup owns up to 256 rows x 256 pixels of Y for the whole of K (f16 / bf16,
+ *                same alignment as 4 and 5; only for matrices whose every tile keeps a weight;
+ *                sub_stripes x col_tiles = the workgroup's tile in units of 16 rows x 16 pixels:
+ *                16 x 16, 8 x 16, 8 x 8, 16 x 4, 4 x 8 or 4 x 4; 0 = the largest that still gives
+ *                about one workgroup per CU).
+ *                0 picks 1 for fp32; 6 for 16-row blocks at least 16 wide when K > 1024; else, while
+ *                at least half of the 16 x 32 tiles of W keep a weight, 7 (every tile keeps one, and
+ *                K <= 256 or N <= 4096), 4 (K <= 256) or 5; else 2.
  *                (3 is not used.)
  *   sub_stripes: kernels 2 and 6, 16-row stripes per wavefront (1, 2 or 4; kernel 6: 2, 4 or 5,
  *                by itself 5 where that saves a workgroup row, else 4);
  *                kernel 5: 2 or 4.
- *   col_tiles  : kernel 2, 16-column tiles per wavefront (2, 4 or 8); kernels 4 and 5: 2 or 4.
+ *   col_tiles  : kernel 2, 16-column tiles per wavefront (2, 4 or 8); kernels 4 and 5: 2 or 4;
+ *                kernel 7: as above.
  *   waves      : wavefronts per workgroup (kernels 2 and 6: producers + 1 .. 16, fewer for shapes
  *                that need many registers; kernel 4 as above).
  *   rows_per_range : kernel 1, output rows owned by one workgroup row (multiple of bh).

@@ -170,14 +170,15 @@ namespace {
 
 // What a call resolves to: the kernel and its launch shape, every field set.
 struct Shape {
-    int kernel = 0;   // 1 vector, 2 gather, 4 small-K dense tiles, 5 chunked dense tiles, 6 block
+    int kernel = 0;   // 1 vector, 2 gather, 4 small-K dense tiles, 5 chunked dense tiles, 6 block, 7 dense tiles through LDS
+    int shape = 0;    // kernel 7: tile shape
     int G = 0, CT = 0, waves = 0, NP = 0, wg_rows = 0, rpr = 0;
     bool resident = false;
 };
 
 // Decides kernel and shape for (handle, N, alignment) and the caller's pins; builds the host image
 // of the layout that shape needs (under the handle's lock).  No device work.
-ubp_status resolve(const ubp_packed *p, int N, bool vec_ok, const ubp_plan &pl, Shape &s) {
+ubp_status resolve(const ubp_packed *p, int N, int64_t ldx_bytes, bool vec_ok, const ubp_plan &pl, Shape &s) {
     int kernel = pl.kernel;
     // the dense-tile kernels need 16-byte pieces of X rows that lie entirely inside or outside the matrix
     const bool tile_able = p->dtype != UBP_F32 && vec_ok && N % 8 == 0;
@@ -197,7 +198,13 @@ ubp_status resolve(const ubp_packed *p, int N, bool vec_ok, const ubp_plan &pl, 
                 const TileLayout &T = get_tile_layout(p);
                 const int kt = (p->K + kStep - 1) / kStep;
                 const bool mostly_full = T.kt_pad != 0 && 2 * T.tiles_nonzero >= (int64_t)T.nstripes * kt;
-                if (mostly_full && p->K <= kTileMaxK) kernel = 4;
+                // Among the dense-tile kernels: where every tile keeps a weight, the one that stages both
+                // operands in LDS for small K or few pixels (there a weight tile fetched once per 64 pixels
+                // is what costs: 4.3 against 5.3 us and 11.8 against 13.8 us on two such layers); else
+                // the small-K kernel or the chunked one, which skip empty tiles.
+                const bool all_full = T.kt_pad != 0 && T.tiles_nonzero == (int64_t)T.nstripes * kt;
+                if (all_full && (p->K <= kTileMaxK || N <= 4096) && (int64_t)p->K * ldx_bytes < (int64_t(1) << 31)) kernel = 7;
+                else if (mostly_full && p->K <= kTileMaxK) kernel = 4;
                 else if (mostly_full && T.kt_pad % 4 == 0) kernel = 5;
                 else kernel = 2;
             } else {
@@ -205,7 +212,7 @@ ubp_status resolve(const ubp_packed *p, int N, bool vec_ok, const ubp_plan &pl, 
             }
         }
     }
-    if (kernel == 3 || kernel < 1 || kernel > 6) return UBP_ERR_INVALID_ARG;
+    if (kernel == 3 || kernel < 1 || kernel > 7) return UBP_ERR_INVALID_ARG;
     if (kernel != 1 && p->dtype == UBP_F32) return UBP_ERR_UNSUPPORTED;
     s.kernel = kernel;
     if (kernel == 1) {
@@ -222,6 +229,37 @@ ubp_status resolve(const ubp_packed *p, int N, bool vec_ok, const ubp_plan &pl, 
         if (rpr < 1) return UBP_ERR_INVALID_ARG;
         if ((p->M + rpr - 1) / rpr > 65535) rpr = (p->M + 65534) / 65535; // grid.y limit
         s.rpr = rpr;
+        return UBP_OK;
+    }
+    if (kernel == 7) {
+        if (!tile_able) return UBP_ERR_UNSUPPORTED;
+        const TileLayout &T = get_tile_layout(p);
+        if (T.kt_pad == 0) return UBP_ERR_UNSUPPORTED;
+        // this kernel multiplies every tile: only for matrices whose every tile keeps a weight
+        if (T.tiles_nonzero != (int64_t)T.nstripes * ((p->K + kStep - 1) / kStep)) return UBP_ERR_UNSUPPORTED;
+        int best = -1;
+        int64_t best_score = -1;
+        for (int sh = 0; sh < kNumGemmShapes; ++sh) {
+            int rows, px;
+            gemm_shape(sh, &rows, &px);
+            if (pl.sub_stripes && pl.sub_stripes * 16 != rows) continue;
+            if (pl.col_tiles && pl.col_tiles * 16 != px) continue;
+            // the largest tile that still gives about one workgroup per CU; else the most workgroups
+            const int64_t wgs = (int64_t)((p->M + rows - 1) / rows) * ((N + px - 1) / px);
+            const int64_t score = wgs >= 190 ? ((int64_t)1 << 40) + (int64_t)rows * px : wgs;
+            if (score > best_score) {
+                best_score = score;
+                best = sh;
+            }
+        }
+        if (best < 0) return UBP_ERR_UNSUPPORTED;
+        int rows, px;
+        gemm_shape(best, &rows, &px);
+        s.shape = best;
+        s.G = rows / 16;
+        s.CT = px / 16;
+        s.wg_rows = (p->M + rows - 1) / rows;
+        s.waves = rows * px >= 128 * 256 ? 8 : 4;
         return UBP_OK;
     }
     if (kernel == 4 || kernel == 5) {
@@ -435,13 +473,14 @@ ubp_status execute(const ubp_packed *p, const void *X_dev, int64_t ldx, int32_t 
         // Layouts are built and uploaded on first use, under the handle's lock.  A repeated call
         // finds everything in place and allocates nothing.
         std::lock_guard<std::mutex> hold(p->lock);
-        ubp_status rc = resolve(p, N, vec_ok, pl, s);
+        ubp_status rc = resolve(p, N, ldx * 2, vec_ok, pl, s);
         if (rc != UBP_OK) return rc;
         switch (s.kernel) {
         case 1: rc = upload_values_f32(p); break;
         case 2: rc = upload_stripe_layout(p, layout_slot(s.G, s.CT)); break;
         case 4:
-        case 5: rc = upload_tile_layout(p); break;
+        case 5:
+        case 7: rc = upload_tile_layout(p); break;
         case 6:
             rc = upload_blk_layout(p, blk_slot(s.G));
             if (rc == UBP_OK && N % 64 != 0) {
@@ -449,7 +488,7 @@ ubp_status execute(const ubp_packed *p, const void *X_dev, int64_t ldx, int32_t 
                 std::memset(&tp, 0, sizeof tp);
                 tp.kernel = 2;
                 tp.col_tiles = 4;
-                rc = resolve(p, N, vec_ok, tp, tail);
+                rc = resolve(p, N, ldx * 2, vec_ok, tp, tail);
                 if (rc == UBP_OK) rc = upload_stripe_layout(p, layout_slot(tail.G, tail.CT));
                 has_tail = true;
             }
@@ -472,7 +511,8 @@ ubp_status execute(const ubp_packed *p, const void *X_dev, int64_t ldx, int32_t 
     case 1: return launch_wros(p, X_dev, ldx, N, Y_dev, ldy, y_dtype, s.rpr, stream, dry);
     case 2: return launch_stripe(stripe_args(p, s, X_dev, ldx, N, Y_dev, ldy, vec_ok, 0), bf16, y_f32, s.G, s.CT, s.waves, stream, dry);
     case 4:
-    case 5: {
+    case 5:
+    case 7: {
         const TileLayout &T = p->tiles;
         TileArgs a = {};
         a.frags = p->d_tiles.frags;
@@ -491,6 +531,7 @@ ubp_status execute(const ubp_packed *p, const void *X_dev, int64_t ldx, int32_t 
         a.n_blocks = (N + 16 * s.CT - 1) / (16 * s.CT);
         a.slices = s.wg_rows;
         a.sps = (T.nstripes + s.wg_rows - 1) / s.wg_rows;
+        if (s.kernel == 7) return launch_gemm(a, bf16, y_f32, s.shape, stream, dry);
         if (s.kernel == 4) return launch_xstat(a, bf16, y_f32, s.CT, T.kt_pad, s.waves, stream, dry);
         return launch_xchunk(a, bf16, y_f32, s.CT, s.G, stream, dry);
     }

@@ -259,6 +259,9 @@ ubp_status launch_blk(const BlkArgs &a, bool bf16, bool y_f32, int G, int waves,
 int blk_max_waves(int G);
 ubp_status launch_xstat(const TileArgs &a, bool bf16, bool y_f32, int CT, int KT, int waves, void *stream, bool dry);
 ubp_status launch_xchunk(const TileArgs &a, bool bf16, bool y_f32, int CT, int SW, void *stream, bool dry);
+constexpr int kNumGemmShapes = 6;
+void gemm_shape(int shape, int *rows, int *pixels);
+ubp_status launch_gemm(const TileArgs &a, bool bf16, bool y_f32, int shape, void *stream, bool dry);
 ubp_status launch_floor(void *stream);
 
 } // namespace ubp

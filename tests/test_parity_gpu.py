@@ -107,10 +107,6 @@ def test_x_stationary_kernel_small_k(shape, dtype):
         for y_dtype in (dtype, "f32"):
             Y = run_spmm(W, dtype, bh, bw, blocks, X, y_dtype, _plan(kernel=4, col_tiles=CT, waves=waves, wg_rows=slices))
             check(Y, Yref, Yabs, dtype, y_dtype)
-    # what ubp_spmm picks by itself for such a layer must be this kernel's result bit for bit
-    Ya = run_spmm(W, dtype, bh, bw, blocks, X, "f32")
-    Yt = run_spmm(W, dtype, bh, bw, blocks, X, "f32", _plan(kernel=4))
-    assert np.array_equal(Ya, Yt)
 
 
 CHUNK_SHAPES = [(64, 300, 200, 4, 4, 0.3), (250, 1000, 136, 8, 8, 0.2), (40, 257, 72, 5, 3, 0.3), (530, 600, 64, 16, 16, 0.15),
@@ -157,18 +153,27 @@ def test_dense_tile_kernels_with_padded_pitches(dtype):
 
 def test_automatic_kernel_choice():
     """What ubp_spmm picks by itself must be the documented kernel's result bit for bit: dense
-    tiles (small-K or chunked kernel) while at least half the 16 x 32 tiles of W keep a weight,
+    tiles (LDS-staged, small-K or chunked kernel) while at least half the 16 x 32 tiles of W keep a weight,
     gathered rows otherwise, and whole blocks as operands for 16-row blocks on a K beyond the ring."""
     M, K, N, bh, bw = 160, 1100, 256, 4, 4
-    blocks, W, X = _layer(M, K, N, bh, bw, 0.25, "bf16", seed=91)
+    blocks, W, X = _layer(M, K, N, bh, bw, 0.25, "bf16", seed=91)         # every tile keeps a weight, few pixels
     Ya = run_spmm(W, "bf16", bh, bw, blocks, X, "f32")
-    assert np.array_equal(Ya, run_spmm(W, "bf16", bh, bw, blocks, X, "f32", _plan(kernel=5)))
+    assert np.array_equal(Ya, run_spmm(W, "bf16", bh, bw, blocks, X, "f32", _plan(kernel=7)))
+    blocks8, W8, X8 = _layer(M, K, 4608, bh, bw, 0.25, "bf16", seed=97)  # many pixels: the chunked kernel
+    p = ubp.pack(W8, "bf16", bh, bw, blocks8, device=0)
+    Xd = torch.zeros((K, 4608), dtype=torch.bfloat16, device="cuda")
+    Yd = torch.zeros((M, 4608), dtype=torch.bfloat16, device="cuda")
+    assert ubp.spmm_prepare(p, Xd.data_ptr(), 4608, 4608, Yd.data_ptr(), 4608, "bf16").kernel == 5
+    p.free()
     blocks, W, X = _layer(M, K, N, bh, bw, 0.01, "bf16", seed=92)         # most tiles empty: gathered rows
     Ya = run_spmm(W, "bf16", bh, bw, blocks, X, "f32")
     assert np.array_equal(Ya, run_spmm(W, "bf16", bh, bw, blocks, X, "f32", _plan(kernel=2)))
-    blocks, W, X = _layer(M, 160, N, bh, bw, 0.3, "f16", seed=94)
+    blocks, W, X = _layer(M, 160, N, bh, bw, 0.3, "f16", seed=94)          # every tile keeps a weight: both operands through LDS
     Ya = run_spmm(W, "f16", bh, bw, blocks, X, "f32")
-    assert np.array_equal(Ya, run_spmm(W, "f16", bh, bw, blocks, X, "f32", _plan(kernel=4)))
+    assert np.array_equal(Ya, run_spmm(W, "f16", bh, bw, blocks, X, "f32", _plan(kernel=7)))
+    blocks, W, X = _layer(M, 160, N, 8, 8, 0.12, "f16", seed=96)           # some tiles empty, most not: the small-K kernel
+    Ya = run_spmm(W, "f16", 8, 8, blocks, X, "f32")
+    assert np.array_equal(Ya, run_spmm(W, "f16", 8, 8, blocks, X, "f32", _plan(kernel=4)))
     blocks, W, X = _layer(M, 160, N, bh, bw, 0.01, "f16", seed=95)
     Ya = run_spmm(W, "f16", bh, bw, blocks, X, "f32")
     assert np.array_equal(Ya, run_spmm(W, "f16", bh, bw, blocks, X, "f32", _plan(kernel=2)))
@@ -203,6 +208,35 @@ def test_block_kernel(shape, dtype):
     for G, waves, NP in [(4, 3, 1), (2, 16, 4), (5, 5, 2), (2, 2, 1), (4, 16, 1), (5, 16, 2)]:
         Y = run_spmm(W, dtype, bh, bw, blocks, X, dtype, _plan(kernel=6, sub_stripes=G, waves=waves, producers=NP))
         check(Y, Yref, Yabs, dtype)
+
+
+GEMM_SHAPES = [(100, 200, 328, 4, 4, 0.5), (270, 700, 520, 4, 4, 0.45), (64, 64, 200, 4, 4, 0.6), (530, 96, 1000, 4, 4, 0.5),
+               (16, 32, 16, 16, 16, 1.0), (300, 257, 72, 2, 1, 0.4), (1040, 160, 264, 4, 4, 0.4), (250, 1000, 136, 8, 8, 0.1)]
+
+
+@pytest.mark.parametrize("shape", GEMM_SHAPES, ids=lambda s: "x".join(map(str, s)))
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+def test_lds_staged_dense_tile_kernel(shape, dtype):
+    """Kernel 7 (both operands staged in LDS, a workgroup owns up to 256 rows x 256 pixels) in every
+    tile shape: row and pixel blocks that hang over the edges, K not a multiple of 32, fewer
+    stages than LDS slots, more than one row block per pixel block; a matrix with tiles that keep
+    nothing is refused."""
+    M, K, N, bh, bw, d = shape
+    blocks, W, X = _layer(M, K, N, bh, bw, d, dtype, seed=M + K + 8)
+    Yref, Yabs = _oracle(W, dtype, bh, bw, blocks, X)
+    p = ubp.pack(W, dtype, bh, bw, blocks, device=0)
+    full = p.info(10) == p.info(11)           # every 16 x 32 tile keeps a weight
+    p.free()
+    assert full == (d >= 0.4)
+    for G, CT in [(0, 0), (16, 16), (8, 16), (8, 8), (16, 4), (4, 8), (4, 4)]:
+        for y_dtype in (dtype, "f32"):
+            plan = _plan(kernel=7, sub_stripes=G, col_tiles=CT)
+            if not full:                                  # the kernel multiplies every tile: refused
+                with pytest.raises(ubp.UBPError):
+                    run_spmm(W, dtype, bh, bw, blocks, X, y_dtype, plan)
+                continue
+            Y = run_spmm(W, dtype, bh, bw, blocks, X, y_dtype, plan)
+            check(Y, Yref, Yabs, dtype, y_dtype)
 
 
 def test_block_kernel_refuses_what_it_cannot_do():
@@ -300,6 +334,7 @@ def test_uneven_row_groups_share_the_lds_ring(dtype):
                                                  ("f16", 4, 128, 4, 4), ("bf16", 4, 256, 8, 8),
                                                  ("f16", 5, 512, 4, 4), ("bf16", 5, 512, 8, 8),
                                                  ("f16", 6, 128, 4, 4), ("bf16", 6, 1280, 16, 16), ("bf16", 6, 512, 16, 32),
+                                                 ("f16", 7, 128, 4, 4), ("bf16", 7, 512, 4, 4),
                                                  ("bf16", 0, 1280, 16, 16), ("f16", 0, 128, 4, 4), ("bf16", 0, 512, 4, 4)])
 def test_identity_x_returns_densified_w_bit_exactly(dtype, kernel, K, bh, bw):
     """X = I: every output is one kept weight times one, plus zeros - no rounding anywhere, so Y
@@ -404,7 +439,7 @@ def test_two_runs_are_bit_identical_and_columns_commute():
     assert np.array_equal(Y3, Y1[:, perm])
 
 
-@pytest.mark.parametrize("kernel", [2, 4, 5, 6])
+@pytest.mark.parametrize("kernel", [2, 4, 5, 6, 7])
 def test_every_mfma_kernel_is_deterministic_and_column_order_free(kernel):
     """No kernel uses atomics on Y and every output element has one fixed summation order, whatever
     the pace of the wavefronts that hand data to each other: repeated runs agree bit for bit, and
@@ -414,6 +449,9 @@ def test_every_mfma_kernel_is_deterministic_and_column_order_free(kernel):
     if kernel == 4:
         K = 256
         blocks, W, X = _layer(M, K, N, bh, bw, 0.25, "bf16", seed=18)
+    if kernel == 7:                                    # (it wants every 16 x 32 tile to keep a weight)
+        bh = bw = 4
+        blocks, W, X = _layer(M, K, N, bh, bw, 0.45, "bf16", seed=19)
     plan = _plan(kernel=kernel)
     Y1 = run_spmm(W, "bf16", bh, bw, blocks, X, "f32", plan)
     for _ in range(3):
