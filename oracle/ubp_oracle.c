@@ -11,8 +11,8 @@
  *
  *   1. validate the block list: every block inside the matrix (the edge rule of Eq. 1)
  *      and no two blocks sharing a cell (the non-overlap constraint of Eq. 2);
- *   2. densify: Wd = 0; for every block, copy its bh x bw cells from W ("weights
- *      outside these blocks are pruned", Section 3.1);
+ *   2. densify: Wd = 0; for every block, copy its bh x bw cells from W (every cell that
+ *      lies in no kept block is zero, Section 3.1);
  *   3. Y[i][j] = sum_k Wd[i][k] * X[k][j], a naive loop nest in double precision that
  *      skips nothing (the worked sum for O_23 in Section 3.3 is one instance of it).
  *

@@ -12,7 +12,7 @@ import oracle                                    # noqa: E402
 import paper_2407_19644_amd as ubp               # noqa: E402
 from synthetic import (CONFIGS, decode_f64, encode, get_config, make_activations, make_layer,   # noqa: E402
                        make_weights, select_blocks)
-from gpu_util import check, run_spmm             # noqa: E402
+from gpu_util import check, run_spmm, to_device  # noqa: E402
 
 pytestmark = pytest.mark.gpu
 
@@ -533,3 +533,32 @@ def test_layer_full_size_other_kernels(name):
     for plan in plans:
         Y = run_spmm(W, cfg.dtype, cfg.bh, cfg.bw, blocks, X, "f32", plan)
         check(Y, Yref, Yabs, cfg.dtype, "f32")
+
+
+@pytest.mark.parametrize("name", ["c1", "c2", "c3", "c4"])
+def test_handle_holds_only_the_layout_that_runs(name):
+    """Device memory of a handle after the automatic call: the canonical arrays plus the one
+    layout that call used.  For the block-sparse layer that is at most three times the canonical
+    arrays; for the layers served from dense tiles it is the densified matrix (padded to whole
+    tiles) beside the canonical arrays' index part."""
+    cfg = get_config(name)
+    blocks, W, X = make_layer(cfg)
+    p = ubp.pack(W, cfg.dtype, cfg.bh, cfg.bw, blocks, device=torch.cuda.current_device())
+    canonical = p.info(7)
+    before = p.info(8)
+    assert before <= canonical                                  # nothing but indptr / indices before the first call
+    Xd = to_device(X, cfg.dtype)
+    Yd = torch.empty((cfg.M, cfg.N), dtype=torch.float32, device="cuda")
+    ubp.spmm(p, Xd.data_ptr(), cfg.N, cfg.N, Yd.data_ptr(), cfg.N, "f32", torch.cuda.current_stream().cuda_stream, None)
+    torch.cuda.synchronize()
+    after = p.info(8)
+    if name == "c4":
+        assert after <= 3 * canonical, (after, canonical)
+    else:
+        dense = (-(-cfg.M // 16) * 16) * (-(-cfg.K // 256) * 256) * 2   # tiles padded to whole chunks of 256 columns
+        assert after <= before + dense + 64 * 1024, (after, before, dense)
+    # a second call allocates nothing more
+    ubp.spmm(p, Xd.data_ptr(), cfg.N, cfg.N, Yd.data_ptr(), cfg.N, "f32", torch.cuda.current_stream().cuda_stream, None)
+    torch.cuda.synchronize()
+    assert p.info(8) == after
+    p.free()
