@@ -33,7 +33,7 @@ typedef enum {
     UBP_ERR_OUT_OF_BOUNDS = 2, /* a block does not lie inside the M x K matrix                 */
     UBP_ERR_OVERLAP = 3,       /* two blocks share a cell (includes duplicates)                */
     UBP_ERR_UNSUPPORTED = 4,   /* valid request this build has no kernel for                   */
-    UBP_ERR_INFEASIBLE = 5,    /* ubp_select_reference could not place the requested blocks    */
+    UBP_ERR_INFEASIBLE = 5,    /* no selection with the requested number of blocks exists      */
     UBP_ERR_ALLOC = 6,         /* host or device allocation failed                             */
     UBP_ERR_DEVICE = 7         /* a HIP call failed, or no usable device                       */
 } ubp_status;
@@ -255,6 +255,74 @@ ubp_status ubp_packed_layout(const ubp_packed *p, int32_t sub_stripes, int32_t c
                              int32_t *row_groups, const int32_t **rg_ptr, const int32_t **rg_order,
                              const uint32_t **stream, int64_t *stream_words,
                              const uint32_t **meta, int64_t *meta_words);
+
+/* ---------------------------------------------------------------------------------------------
+ * Block selection on the host (Sections 3.1, 3.2 and 4.1): which blocks of a dense layer to keep.
+ * All pointers are host pointers; nothing here touches a device.
+ *
+ * Candidates.  The K columns of the M x K matrix form K / bw groups of bw consecutive columns
+ * (one input channel each; a remainder of K mod bw columns belongs to no candidate).  Candidate
+ * k = i + M * j is the bh x bw block with origin (row i, column j * bw), so the candidates of one
+ * column group are consecutive in k and there are b = M * (K / bw) of them (Section 3.1).  Two
+ * candidates of one group overlap iff their k differ by less than N = bh, which is the only
+ * constraint between kept blocks (Eq. 2).
+ *
+ * Scores are doubles, finite or -inf; -inf marks a candidate that may never be kept.  A selector
+ * given NaN or +inf returns UBP_ERR_INVALID_ARG.  Equal scores: the lower k wins.
+ */
+
+/*
+ * Importance scores (Eq. 1 with the l1 norm): S[i + M*j] = sum of |W| over the block, -inf where
+ * the block would cross the bottom edge (i + bh > M) and, if aligned != 0, where i is not a
+ * multiple of bh (which turns every selector below into aligned block-wise pruning; remark after
+ * Eq. 2).  W: row-major M x K, pitch ldw elements, read in full.  S: b = M * (K / bw) doubles,
+ * caller-allocated; b is passed for checking.
+ */
+ubp_status ubp_block_scores(const void *W_host, ubp_dtype dtype, int64_t ldw, int32_t M, int32_t K,
+                            int32_t bh, int32_t bw, int32_t aligned, double *S, int64_t b);
+
+/*
+ * The three selectors share one signature.  S: b scores (not modified).  N: block height in
+ * candidates (bh).  m: blocks wanted.  I: caller-allocated, m entries; receives *count candidate
+ * indices.  *count can be below m for the first two when no candidate with a score above -inf is
+ * left; ubp_select_optimal returns either m indices or UBP_ERR_INFEASIBLE.
+ *
+ * ubp_select_greedy  (Section 3.2, Eq. 3): best remaining candidate first; a kept k shuts out
+ *     k-N+1 .. k+N-1.  I is in order of selection.  O(b log b).
+ * ubp_select_bed     (Section 4.1, Algorithms 1 and 2): block expansion -- the best entry of the
+ *     score list is kept m times, each time the N-1 entries before it are re-scored as the blocks
+ *     that join across the gap and the entry with its N-1 successors leaves the list -- then
+ *     block division of the expanded runs into blocks of N.  I ascending.  O(b + m N log b).
+ * ubp_select_optimal (Section 3.2, Eq. 4): the selection of exactly m non-overlapping candidates
+ *     with the largest total score; of equal totals the one Eq. 4's strict comparison reaches.
+ *     I ascending.  O(b m) time and b m bits of memory; UBP_ERR_UNSUPPORTED above 2 GiB of those.
+ */
+ubp_status ubp_select_greedy(const double *S, int64_t b, int32_t N, int64_t m, int64_t *I, int64_t *count);
+ubp_status ubp_select_bed(const double *S, int64_t b, int32_t N, int64_t m, int64_t *I, int64_t *count);
+ubp_status ubp_select_optimal(const double *S, int64_t b, int32_t N, int64_t m, int64_t *I, int64_t *count);
+
+/* Candidate indices -> block origins: blocks[t] = (I[t] mod M, (I[t] div M) * bw). */
+ubp_status ubp_selection_to_blocks(const int64_t *I, int64_t count, int32_t M, int32_t bw, ubp_block *blocks);
+
+/*
+ * Scores, one selector and the conversion in one call: the block list ubp_pack takes, with
+ * ubp_target_block_count(M, K, bh, bw, density) blocks (fewer if the selector runs out).
+ * method: 0 greedy, 1 expansion + division, 2 optimal.  aligned as in ubp_block_scores.
+ * UBP_ERR_INVALID_ARG if capacity is below the target count (*out_nb then holds it).
+ */
+ubp_status ubp_select_blocks(const void *W_host, ubp_dtype dtype, int64_t ldw, int32_t M, int32_t K,
+                             int32_t bh, int32_t bw, double density, int32_t method, int32_t aligned,
+                             ubp_block *out, int64_t capacity, int64_t *out_nb);
+
+/*
+ * Efficacy of an unaligned selection (Section 5.1, Eq. 5): (|W_ubp| - |W_abp|) / (|W_ep| - |W_abp|)
+ * with |W_x| the l1 norm of the weights x keeps; element-wise pruning (ep) keeps the nb*bh*bw
+ * largest magnitudes.  l1 (optional, 3 doubles) receives |W_ubp|, |W_abp|, |W_ep|.  Blocks outside
+ * the matrix: UBP_ERR_OUT_OF_BOUNDS; overlapping blocks count each weight once.
+ */
+ubp_status ubp_selection_efficacy(const void *W_host, ubp_dtype dtype, int64_t ldw, int32_t M, int32_t K,
+                                  int32_t bh, int32_t bw, const ubp_block *ubp_blocks, int64_t nb,
+                                  const ubp_block *abp_blocks, int64_t nb_abp, double *l1, double *efficacy);
 
 /*
  * Enqueues an empty kernel (one wavefront, no memory access) on hip_stream: what a launch costs

@@ -24,7 +24,9 @@ _NP_OF = {"f32": np.float32, "f16": np.float16, "bf16": np.uint16}
 EXPORTS = ("ubp_target_block_count", "ubp_select_reference", "ubp_pack", "ubp_packed_indptr",
            "ubp_packed_indices", "ubp_packed_values", "ubp_spmm", "ubp_spmm_plan", "ubp_packed_info",
            "ubp_packed_free", "ubp_status_string", "ubp_packed_device_error", "ubp_packed_layout",
-           "ubp_spmm_prepare", "ubp_launch_floor")
+           "ubp_spmm_prepare", "ubp_launch_floor", "ubp_block_scores", "ubp_select_greedy", "ubp_select_bed",
+           "ubp_select_optimal", "ubp_selection_to_blocks", "ubp_select_blocks", "ubp_selection_efficacy")
+SELECT_METHODS = {"greedy": 0, "bed": 1, "optimal": 2}
 
 
 class UBPError(RuntimeError):
@@ -81,6 +83,18 @@ def load_library():
     L.ubp_spmm_prepare.restype = ctypes.c_int
     L.ubp_launch_floor.argtypes = [vp]
     L.ubp_launch_floor.restype = ctypes.c_int
+    L.ubp_block_scores.argtypes = [vp, ctypes.c_int, i64, i32, i32, i32, i32, i32, vp, i64]
+    L.ubp_block_scores.restype = ctypes.c_int
+    for f in (L.ubp_select_greedy, L.ubp_select_bed, L.ubp_select_optimal):
+        f.argtypes = [vp, i64, i32, i64, vp, pi64]
+        f.restype = ctypes.c_int
+    L.ubp_selection_to_blocks.argtypes = [vp, i64, i32, i32, vp]
+    L.ubp_selection_to_blocks.restype = ctypes.c_int
+    L.ubp_select_blocks.argtypes = [vp, ctypes.c_int, i64, i32, i32, i32, i32, dbl, i32, i32, vp, i64, pi64]
+    L.ubp_select_blocks.restype = ctypes.c_int
+    L.ubp_selection_efficacy.argtypes = [vp, ctypes.c_int, i64, i32, i32, i32, i32, vp, i64, vp, i64, vp,
+                                         ctypes.POINTER(dbl)]
+    L.ubp_selection_efficacy.restype = ctypes.c_int
     L.ubp_packed_free.argtypes = [vp]
     L.ubp_packed_free.restype = None
     L.ubp_status_string.argtypes = [ctypes.c_int]
@@ -110,6 +124,91 @@ def select_reference(M, K, bh, bw, density, seed, mode=0, zipf_s=0.0):
     if rc != UBP_OK:
         raise UBPError(rc, "ubp_select_reference")
     return out[:nb.value].copy()
+
+
+def _weights(W_host, dtype):
+    W = np.asarray(W_host)
+    if W.ndim != 2 or W.dtype != _NP_OF[dtype] or W.strides[1] != W.itemsize or W.strides[0] % W.itemsize:
+        raise ValueError("W must be a row-major 2-D array of %s" % _NP_OF[dtype].__name__)
+    return W
+
+
+def block_scores(W_host, dtype, bh, bw, aligned=False):
+    """ubp_block_scores -> float64 array of b = M * (K // bw) scores, candidate k = i + M * j."""
+    W = _weights(W_host, dtype)
+    S = np.empty(W.shape[0] * (W.shape[1] // bw), dtype=np.float64)
+    rc = load_library().ubp_block_scores(W.ctypes.data, DTYPES[dtype], W.strides[0] // W.itemsize, W.shape[0],
+                                         W.shape[1], bh, bw, int(bool(aligned)), S.ctypes.data, S.size)
+    if rc != UBP_OK:
+        raise UBPError(rc, "ubp_block_scores")
+    return S
+
+
+def _select(name, S, N, m):
+    S = np.ascontiguousarray(S, dtype=np.float64)
+    I = np.zeros(max(int(m), 1), dtype=np.int64)
+    count = ctypes.c_int64(0)
+    rc = getattr(load_library(), name)(S.ctypes.data, S.size, int(N), int(m), I.ctypes.data, ctypes.byref(count))
+    if rc != UBP_OK:
+        raise UBPError(rc, name)
+    return I[:count.value].copy()
+
+
+def select_greedy(S, N, m):
+    """ubp_select_greedy -> int64 candidate indices in order of selection."""
+    return _select("ubp_select_greedy", S, N, m)
+
+
+def select_bed(S, N, m):
+    """ubp_select_bed -> int64 candidate indices, ascending."""
+    return _select("ubp_select_bed", S, N, m)
+
+
+def select_optimal(S, N, m):
+    """ubp_select_optimal -> int64 candidate indices, ascending; UBPError(5) if no m blocks fit."""
+    return _select("ubp_select_optimal", S, N, m)
+
+
+def selection_to_blocks(I, M, bw):
+    """ubp_selection_to_blocks -> int32 array [count, 2] of (r, c)."""
+    I = np.ascontiguousarray(I, dtype=np.int64)
+    out = np.zeros((max(I.size, 1), 2), dtype=np.int32)
+    rc = load_library().ubp_selection_to_blocks(I.ctypes.data, I.size, int(M), int(bw), out.ctypes.data)
+    if rc != UBP_OK:
+        raise UBPError(rc, "ubp_selection_to_blocks")
+    return out[:I.size].copy()
+
+
+def select_blocks(W_host, dtype, bh, bw, density, method="bed", aligned=False):
+    """ubp_select_blocks -> int32 array [nb, 2] of (r, c)."""
+    W = _weights(W_host, dtype)
+    L = load_library()
+    need = L.ubp_target_block_count(W.shape[0], W.shape[1], bh, bw, float(density))
+    if need < 0:
+        raise UBPError(1, "ubp_select_blocks")
+    out = np.zeros((max(int(need), 1), 2), dtype=np.int32)
+    nb = ctypes.c_int64(0)
+    rc = L.ubp_select_blocks(W.ctypes.data, DTYPES[dtype], W.strides[0] // W.itemsize, W.shape[0], W.shape[1], bh, bw,
+                             float(density), SELECT_METHODS[method], int(bool(aligned)), out.ctypes.data, int(need),
+                             ctypes.byref(nb))
+    if rc != UBP_OK:
+        raise UBPError(rc, "ubp_select_blocks")
+    return out[:nb.value].copy()
+
+
+def selection_efficacy(W_host, dtype, bh, bw, ubp_blocks, abp_blocks):
+    """ubp_selection_efficacy -> (efficacy, (l1_ubp, l1_abp, l1_ep))."""
+    W = _weights(W_host, dtype)
+    u = np.ascontiguousarray(np.asarray(ubp_blocks, dtype=np.int32).reshape(-1, 2))
+    a = np.ascontiguousarray(np.asarray(abp_blocks, dtype=np.int32).reshape(-1, 2))
+    l1 = np.zeros(3, dtype=np.float64)
+    eff = ctypes.c_double(0.0)
+    rc = load_library().ubp_selection_efficacy(W.ctypes.data, DTYPES[dtype], W.strides[0] // W.itemsize, W.shape[0],
+                                               W.shape[1], bh, bw, u.ctypes.data, u.shape[0], a.ctypes.data, a.shape[0],
+                                               l1.ctypes.data, ctypes.byref(eff))
+    if rc != UBP_OK:
+        raise UBPError(rc, "ubp_selection_efficacy")
+    return eff.value, tuple(l1.tolist())
 
 
 class Packed:

@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libubp.so")
-HOST_SOURCES = ["ubp_host.cpp", "ubp_layouts.cpp"]
+HOST_SOURCES = ["ubp_host.cpp", "ubp_layouts.cpp", "ubp_select.cpp"]
 HIP_SOURCES = ["ubp_api.hip", "ubp_wros.hip", "ubp_stripe.hip", "ubp_blk.hip", "ubp_tile.hip", "ubp_gemm.hip"]
 COMMON = ["-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-result"]
 # packed-fp32 VALU forms are switched off for every device function in this library

@@ -562,3 +562,22 @@ def test_handle_holds_only_the_layout_that_runs(name):
     torch.cuda.synchronize()
     assert p.info(8) == after
     p.free()
+
+
+@pytest.mark.parametrize("method", ["greedy", "bed", "optimal"])
+def test_selected_blocks_through_the_product(method):
+    """Block lists chosen from the weights themselves (Sections 3.2 and 4.1) instead of sampled
+    origins: magnitude-driven masks cluster differently from uniform ones, and the product must
+    not care."""
+    rng = np.random.default_rng(31)
+    for M, K, N, bh, bw, dtype, density in ((192, 256, 200, 4, 1, "f16", 0.3), (256, 2048, 128, 16, 16, "bf16", 0.1),
+                                            (96, 160, 72, 8, 2, "f32", 0.25)):
+        W64 = rng.standard_normal((M, K)) * np.exp(rng.standard_normal((M, 1)))     # some rows matter more
+        W = encode(W64, dtype)
+        blocks = ubp.select_blocks(W, dtype, bh, bw, density, method)
+        assert len(blocks) == ubp.target_block_count(M, K, bh, bw, density)
+        X = make_activations(K, N, 5, dtype, "relu_normal")
+        Yref, Yabs = oracle.spmm(decode_f64(W, dtype), bh, bw, blocks, decode_f64(X, dtype), want_abs=True)
+        for y_dtype in sorted({dtype, "f32"}):
+            Y = run_spmm(W, dtype, bh, bw, blocks, X, y_dtype)
+            check(Y, Yref, Yabs, dtype, y_dtype)

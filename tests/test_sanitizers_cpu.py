@@ -1,7 +1,7 @@
 """Host code under AddressSanitizer and UndefinedBehaviorSanitizer (CPU only).
 
 The library's host side (test-mask generator, offline weight transform, builders of the kernels'
-private layouts, accessors) and the C oracle are compiled with gcc and -fsanitize=address,undefined
+private layouts, accessors, block selectors) and the C oracle are compiled with gcc and -fsanitize=address,undefined
 into one small driver program together with a stub for the device half of the library, and the
 driver walks through packing, every layout and the error paths of the five benchmark-shaped
 layers at reduced size.  Any out-of-bounds access, leak, signed overflow or misaligned access in
@@ -86,6 +86,31 @@ static int one(int M, int K, int bh, int bw, double density, int mode, ubp_dtype
     CHECK(ubp_pack(W.data(), dt, M, K, K, bh, bw, &out, 1, UBP_HOST_ONLY, &q) == UBP_ERR_OUT_OF_BOUNDS && !q);
     CHECK(ubp_pack(W.data(), dt, M, K, K, bh, bw, blocks.data(), nb, 0, &q) == UBP_ERR_DEVICE && !q);   // the stub has no device
     ubp_packed_free(p);
+    // block selection on the same weights (16-bit patterns read as numbers; fp32 patterns are finite too)
+    if (dt != UBP_F32) {
+        const int64_t b = (int64_t)M * (K / bw);
+        std::vector<double> S((size_t)b);
+        CHECK(ubp_block_scores(W.data(), dt, K, M, K, bh, bw, 0, S.data(), b) == UBP_OK);
+        std::vector<int64_t> I((size_t)nb + 1);
+        std::vector<ubp_block> chosen((size_t)nb + 1);
+        for (int method = 0; method < 3; ++method) {
+            int64_t count = 0;
+            ubp_status rc = method == 0 ? ubp_select_greedy(S.data(), b, bh, nb, I.data(), &count)
+                          : method == 1 ? ubp_select_bed(S.data(), b, bh, nb, I.data(), &count)
+                                        : ubp_select_optimal(S.data(), b, bh, nb, I.data(), &count);
+            CHECK(rc == UBP_OK || (method == 2 && (rc == UBP_ERR_INFEASIBLE || rc == UBP_ERR_UNSUPPORTED)));
+            if (rc != UBP_OK) continue;
+            CHECK(count <= nb);
+            CHECK(ubp_selection_to_blocks(I.data(), count, M, bw, chosen.data()) == UBP_OK);
+            ubp_packed *s = nullptr;
+            CHECK(ubp_pack(W.data(), dt, M, K, K, bh, bw, chosen.data(), count, UBP_HOST_ONLY, &s) == UBP_OK);
+            double eff = 0.0, l1[3];
+            CHECK(ubp_selection_efficacy(W.data(), dt, K, M, K, bh, bw, chosen.data(), count, blocks.data(), nb, l1, &eff) == UBP_OK);
+            ubp_packed_free(s);
+        }
+        int64_t got = 0;
+        CHECK(ubp_select_blocks(W.data(), dt, K, M, K, bh, bw, density, 1, 1, chosen.data(), nb, &got) == UBP_OK && got <= nb);
+    }
     return 0;
 }
 
@@ -117,7 +142,8 @@ def test_host_code_under_asan_and_ubsan(tmp_path):
     san = ["-fsanitize=address,undefined", "-fno-sanitize-recover=undefined", "-fno-omit-frame-pointer", "-g", "-O1"]
     subprocess.check_call(["gcc", "-std=c99", "-c", os.path.join(ROOT, "oracle", "ubp_oracle.c"), "-o", str(orc)] + san)
     subprocess.check_call(["g++", "-std=c++17", "-I", os.path.join(ROOT, "include"), "-I", CSRC, str(drv),
-                           os.path.join(CSRC, "ubp_host.cpp"), os.path.join(CSRC, "ubp_layouts.cpp"), str(orc),
+                           os.path.join(CSRC, "ubp_host.cpp"), os.path.join(CSRC, "ubp_layouts.cpp"),
+                           os.path.join(CSRC, "ubp_select.cpp"), str(orc),
                            "-o", str(exe), "-static-libasan", "-static-libubsan", "-pthread"] + san)
     env = dict(os.environ)
     env["ASAN_OPTIONS"] = "detect_leaks=1:abort_on_error=0"
