@@ -33,7 +33,8 @@ HBM_PEAK_GBS = 8000.0            # MI355X HBM3E, published
 MFMA_PEAK_TFLOPS = 2500.0        # dense bf16 / fp16 MFMA, published
 INFINITY_CACHE_BYTES = 256 << 20
 MIN_TIMED_MS = 50.0
-KERNEL_NAMES = {1: "wros_kernel", 2: "stripe_kernel", 4: "xstat_kernel", 5: "xchunk_kernel", 6: "blk_kernel"}
+KERNEL_NAMES = {1: "wros_kernel", 2: "stripe_kernel", 3: "naive_kernel", 4: "xstat_kernel", 5: "xchunk_kernel", 6: "blk_kernel",
+                7: "gemm_kernel"}
 
 
 def algorithmic_bytes(cfg, nb, N, y_bytes):
@@ -335,6 +336,15 @@ def main():
             e.update({"abp_kernel_us": ra["kernel_us"], "abp_kernel": ra["kernel"], "ubp_over_abp": r["kernel_us"] / ra["kernel_us"],
                       "block": r["block"], "density": c.density})
             per["%s/y_%s" % (c.name, r["y_dtype"])] = e
+            # the vector kernel's two dataflows on the same layer (Section 5.2): weights rotated and
+            # outputs stationary, on unaligned and on aligned origins, against the register-shifting one
+            if c.bw == 1:
+                vw = measure(c, lay, st, args.warmup, None, {"kernel": 1}, use_graph, args.hot, verify_rows=8)
+                va = measure(ca, make_layer(ca), st, args.warmup, None, {"kernel": 1}, use_graph, args.hot, verify_rows=8)
+                vn = measure(c, lay, st, args.warmup, None, {"kernel": 3}, use_graph, args.hot, verify_rows=8)
+                e["vector_dataflows_us"] = {"ubp_wros": vw["kernel_us"], "abp": va["kernel_us"], "ubp_naive": vn["kernel_us"],
+                                            "wros_over_abp": vw["kernel_us"] / va["kernel_us"],
+                                            "naive_over_wros": vn["kernel_us"] / vw["kernel_us"]}
     out = {
         "metric": "UBP SpMM effective GFLOP/s (kept-weight FLOPs) + % of HBM/MFMA roofline",
         "value": head["gflops_kept"], "unit": "GFLOP/s",

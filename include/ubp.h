@@ -140,6 +140,10 @@ ubp_status ubp_spmm(const ubp_packed *p, const void *X_dev, int64_t ldx, int32_t
  * "choose automatically"; an impossible combination returns UBP_ERR_UNSUPPORTED.
  *   kernel     : 1 = vector-ALU kernel that follows the WROS dataflow literally (any
  *                dtype, bh <= 16).
+ *                3 = the same kernel with the dataflow the weight rotation replaces (Section
+ *                3.3): one output row stored per start row, the other accumulator rows shifted
+ *                up by one.  Never chosen automatically; it exists so that the cost of the
+ *                shifting can be measured next to kernel 1 (same results bit for bit).
  *                2 = MFMA kernel on aligned 16-row stripes that gathers the rows of X a row
  *                group needs (f16 / bf16).
  *                4, 5 and 7 = MFMA kernels that use W as zero-filled 16 x 32 operand tiles; 4 and 5
@@ -172,7 +176,7 @@ ubp_status ubp_spmm(const ubp_packed *p, const void *X_dev, int64_t ldx, int32_t
  *                kernel 7: as above.
  *   waves      : wavefronts per workgroup (kernels 2 and 6: producers + 1 .. 16, fewer for shapes
  *                that need many registers; kernel 4 as above).
- *   rows_per_range : kernel 1, output rows owned by one workgroup row (multiple of bh).
+ *   rows_per_range : kernels 1 and 3, output rows owned by one workgroup row (multiple of bh).
  *   producers  : kernels 2 and 6, wavefronts of a workgroup that stage X into LDS (1, 2 or 4);
  *                the others each own a row group.
  *   wg_rows    : kernels 2 and 6, workgroups that share one column tile (each takes a share of

@@ -212,10 +212,10 @@ ubp_status resolve(const ubp_packed *p, int N, int64_t ldx_bytes, bool vec_ok, c
             }
         }
     }
-    if (kernel == 3 || kernel < 1 || kernel > 7) return UBP_ERR_INVALID_ARG;
-    if (kernel != 1 && p->dtype == UBP_F32) return UBP_ERR_UNSUPPORTED;
+    if (kernel < 1 || kernel > 7) return UBP_ERR_INVALID_ARG;
+    if (kernel != 1 && kernel != 3 && p->dtype == UBP_F32) return UBP_ERR_UNSUPPORTED;
     s.kernel = kernel;
-    if (kernel == 1) {
+    if (kernel == 1 || kernel == 3) {
         if (p->bh > 16) return UBP_ERR_UNSUPPORTED;
         int rpr = pl.rows_per_range;
         if (rpr == 0) {
@@ -476,7 +476,8 @@ ubp_status execute(const ubp_packed *p, const void *X_dev, int64_t ldx, int32_t 
         ubp_status rc = resolve(p, N, ldx * 2, vec_ok, pl, s);
         if (rc != UBP_OK) return rc;
         switch (s.kernel) {
-        case 1: rc = upload_values_f32(p); break;
+        case 1:
+        case 3: rc = upload_values_f32(p); break;
         case 2: rc = upload_stripe_layout(p, layout_slot(s.G, s.CT)); break;
         case 4:
         case 5:
@@ -508,7 +509,8 @@ ubp_status execute(const ubp_packed *p, const void *X_dev, int64_t ldx, int32_t 
     }
 
     switch (s.kernel) {
-    case 1: return launch_wros(p, X_dev, ldx, N, Y_dev, ldy, y_dtype, s.rpr, stream, dry);
+    case 1:
+    case 3: return launch_wros(p, X_dev, ldx, N, Y_dev, ldy, y_dtype, s.rpr, s.kernel == 3, stream, dry);
     case 2: return launch_stripe(stripe_args(p, s, X_dev, ldx, N, Y_dev, ldy, vec_ok, 0), bf16, y_f32, s.G, s.CT, s.waves, stream, dry);
     case 4:
     case 5:

@@ -252,7 +252,7 @@ ubp_status upload_tile_layout(const ubp_packed *p);
 // Launchers.  `dry` only raises the kernels' dynamic LDS limit on the current device (what a
 // first launch of a shape would do), so that a later launch is nothing but a launch.
 ubp_status launch_wros(const ubp_packed *p, const void *X, int64_t ldx, int N, void *Y, int64_t ldy, ubp_dtype y_dtype,
-                       int rpr, void *stream, bool dry);
+                       int rpr, bool naive, void *stream, bool dry);
 ubp_status launch_stripe(const StripeArgs &a, bool bf16, bool y_f32, int G, int CT, int waves, void *stream, bool dry);
 int stripe_max_waves(int G, int CT);
 ubp_status launch_blk(const BlkArgs &a, bool bf16, bool y_f32, int G, int waves, void *stream, bool dry);

@@ -60,15 +60,65 @@ __global__ __launch_bounds__(256) void wros_kernel(const int32_t *__restrict__ i
     }
 }
 
+// ------------------------------------------------------------------ naive dataflow (comparison only)
+// The dataflow the weight rotation replaces (Section 3.3): accumulator row t always belongs to
+// the output row t below the current start row.  After start row i is done, row 0 is stored, rows
+// 1 .. BH-1 move up by one register row and the last one is cleared.  Same grid, same ranges, same
+// loads and the same order of additions per output element as wros_kernel; the weights are read
+// from the rotated array at the slot their row has there.
+template <typename TX, typename TY, int BH, int VEC>
+__global__ __launch_bounds__(256) void naive_kernel(const int32_t *__restrict__ indptr, const int32_t *__restrict__ indices,
+                                                   const float *__restrict__ vals, const TX *__restrict__ X, int64_t ldx,
+                                                   TY *__restrict__ Y, int64_t ldy, int M, int N, int bw, int rpr) {
+    const int col = (blockIdx.x * 256 + threadIdx.x) * VEC;
+    if (col >= N) return;
+    const int lo = blockIdx.y * rpr;
+    const int hi = min(lo + rpr, M);
+    const int last_start = M - BH;
+    float acc[BH][VEC];
+#pragma unroll
+    for (int t = 0; t < BH; ++t)
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) acc[t][v] = 0.f;
+
+    for (int i = max(0, lo - BH + 1); i < hi; ++i) {
+        if (i <= last_start) {
+            const int u = i % BH; // slot of the block's first row in the rotated array
+            const int b1 = indptr[i + 1];
+            for (int b = indptr[i]; b < b1; ++b) {
+                const int c = indices[b];
+                const float *w = vals + (int64_t)b * bw * BH;
+                for (int q = 0; q < bw; ++q) {
+                    float x[VEC];
+                    load_row<TX, VEC>(X + (int64_t)(c + q) * ldx + col, x);
+#pragma unroll
+                    for (int t = 0; t < BH; ++t) {
+                        const float wt = w[q * BH + (u + t >= BH ? u + t - BH : u + t)];
+#pragma unroll
+                        for (int v = 0; v < VEC; ++v) acc[t][v] = fmaf(wt, x[v], acc[t][v]);
+                    }
+                }
+            }
+        }
+        if (i >= lo) store_row<TY, VEC>(Y + (int64_t)i * ldy + col, acc[0]);
+#pragma unroll
+        for (int t = 0; t + 1 < BH; ++t)
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) acc[t][v] = acc[t + 1][v];
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) acc[BH - 1][v] = 0.f;
+    }
+}
+
 template <typename TX, typename TY, int VEC>
 ubp_status launch_wros_bh(const ubp_packed *p, const void *X, int64_t ldx, int N, void *Y, int64_t ldy, int rpr,
-                          hipStream_t st) {
+                          bool naive, hipStream_t st) {
     dim3 grid((unsigned)((N + 256 * VEC - 1) / (256 * VEC)), (unsigned)((p->M + rpr - 1) / rpr));
 #define UBP_WROS_CASE(BH)                                                                                              \
     case BH:                                                                                                           \
-        hipLaunchKernelGGL((wros_kernel<TX, TY, BH, VEC>), grid, dim3(256), 0, st, p->d_indptr, p->d_indices,         \
-                           p->d_values_f32, static_cast<const TX *>(X), ldx, static_cast<TY *>(Y), ldy, p->M, N, p->bw, \
-                           rpr);                                                                                       \
+        hipLaunchKernelGGL((naive ? (naive_kernel<TX, TY, BH, VEC>) : (wros_kernel<TX, TY, BH, VEC>)), grid, dim3(256), 0, \
+                           st, p->d_indptr, p->d_indices, p->d_values_f32, static_cast<const TX *>(X), ldx,           \
+                           static_cast<TY *>(Y), ldy, p->M, N, p->bw, rpr);                                            \
         break;
     switch (p->bh) {
         UBP_WROS_CASE(1) UBP_WROS_CASE(2) UBP_WROS_CASE(3) UBP_WROS_CASE(4) UBP_WROS_CASE(5) UBP_WROS_CASE(6)
@@ -82,30 +132,30 @@ ubp_status launch_wros_bh(const ubp_packed *p, const void *X, int64_t ldx, int N
 
 template <typename TX, typename TY>
 ubp_status launch_wros_t(const ubp_packed *p, const void *X, int64_t ldx, int N, void *Y, int64_t ldy, int rpr,
-                         hipStream_t st) {
+                         bool naive, hipStream_t st) {
     // 4 columns per thread when every row of X and Y can be accessed as an aligned 4-vector
     const bool vec = (N % 4 == 0) && (ldx % 4 == 0) && (ldy % 4 == 0) &&
                      (reinterpret_cast<uintptr_t>(X) % (4 * sizeof(TX)) == 0) &&
                      (reinterpret_cast<uintptr_t>(Y) % (4 * sizeof(TY)) == 0) && N >= 2048;
-    return vec ? launch_wros_bh<TX, TY, 4>(p, X, ldx, N, Y, ldy, rpr, st)
-               : launch_wros_bh<TX, TY, 1>(p, X, ldx, N, Y, ldy, rpr, st);
+    return vec ? launch_wros_bh<TX, TY, 4>(p, X, ldx, N, Y, ldy, rpr, naive, st)
+               : launch_wros_bh<TX, TY, 1>(p, X, ldx, N, Y, ldy, rpr, naive, st);
 }
 
 } // namespace
 
 ubp_status launch_wros(const ubp_packed *p, const void *X, int64_t ldx, int N, void *Y, int64_t ldy, ubp_dtype y_dtype,
-                       int rpr, void *stream, bool dry) {
+                       int rpr, bool naive, void *stream, bool dry) {
     if (dry) return p->bh > 16 ? UBP_ERR_UNSUPPORTED : UBP_OK; // static LDS only: nothing to prepare
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (p->bh > 16) return UBP_ERR_UNSUPPORTED;
     switch (p->dtype) {
-    case UBP_F32: return launch_wros_t<float, float>(p, X, ldx, N, Y, ldy, rpr, st);
+    case UBP_F32: return launch_wros_t<float, float>(p, X, ldx, N, Y, ldy, rpr, naive, st);
     case UBP_F16:
-        return y_dtype == UBP_F32 ? launch_wros_t<_Float16, float>(p, X, ldx, N, Y, ldy, rpr, st)
-                                  : launch_wros_t<_Float16, _Float16>(p, X, ldx, N, Y, ldy, rpr, st);
+        return y_dtype == UBP_F32 ? launch_wros_t<_Float16, float>(p, X, ldx, N, Y, ldy, rpr, naive, st)
+                                  : launch_wros_t<_Float16, _Float16>(p, X, ldx, N, Y, ldy, rpr, naive, st);
     case UBP_BF16:
-        return y_dtype == UBP_F32 ? launch_wros_t<__bf16, float>(p, X, ldx, N, Y, ldy, rpr, st)
-                                  : launch_wros_t<__bf16, __bf16>(p, X, ldx, N, Y, ldy, rpr, st);
+        return y_dtype == UBP_F32 ? launch_wros_t<__bf16, float>(p, X, ldx, N, Y, ldy, rpr, naive, st)
+                                  : launch_wros_t<__bf16, __bf16>(p, X, ldx, N, Y, ldy, rpr, naive, st);
     }
     return UBP_ERR_INVALID_ARG;
 }

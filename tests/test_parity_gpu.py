@@ -60,6 +60,9 @@ def test_wros_kernel_small(shape, dtype):
         for rpr in (0, bh, 3 * bh):
             Y = run_spmm(W, dtype, bh, bw, blocks, X, y_dtype, _plan(kernel=1, rows_per_range=rpr))
             check(Y, Yref, Yabs, dtype, y_dtype)
+            # the dataflow without weight rotation (Section 3.3): same additions in the same order
+            Yn = run_spmm(W, dtype, bh, bw, blocks, X, y_dtype, _plan(kernel=3, rows_per_range=rpr))
+            assert np.array_equal(Yn, Y)
 
 
 @pytest.mark.parametrize("shape", SMALL + [(90, 64, 50, 20, 3, 0.25)], ids=lambda s: "x".join(map(str, s)))
@@ -259,7 +262,7 @@ def test_block_kernel_refuses_what_it_cannot_do():
     with pytest.raises(ubp.UBPError):
         run_spmm(W, "f32", 4, 4, blocks, X, "f32", _plan(kernel=6))
     with pytest.raises(ubp.UBPError):
-        run_spmm(W, "f32", 4, 4, blocks, X, "f32", _plan(kernel=3))       # there is no kernel 3
+        run_spmm(W, "f32", 4, 4, blocks, X, "f32", _plan(kernel=8))       # there is no kernel 8
 
 
 def test_chunked_kernel_refuses_what_it_cannot_do():
