@@ -44,11 +44,14 @@ def algorithmic_bytes(cfg, nb, N, y_bytes):
     return w + cfg.K * N * esz + cfg.M * N * y_bytes
 
 
+PROFILING = False      # --profile: one replay per measurement, no launch-floor / copy-bandwidth legs
+
+
 def timed_replays(run_once, stream, est_ms):
     """Replays until MIN_TIMED_MS are covered.  Returns (wall seconds of all replays, list of
     per-replay event milliseconds)."""
     import torch
-    reps = int(min(2000, max(3, np.ceil(MIN_TIMED_MS / max(est_ms, 1e-3)))))
+    reps = 1 if PROFILING else int(min(2000, max(3, np.ceil(MIN_TIMED_MS / max(est_ms, 1e-3)))))
     ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -279,11 +282,16 @@ def main():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain elementwise kernel over 256 MiB 3 times (reads 256 MiB, writes 256 MiB: "
                          "known traffic, to scale rocprofv3 byte counters)")
+    ap.add_argument("--profile", action="store_true",
+                    help="for runs under rocprofv3, where every dispatch is slow: one replay per measurement and no "
+                         "launch-floor / copy-bandwidth legs (their fields are null)")
     ap.add_argument("--kernel", type=int, default=0)
     ap.add_argument("--G", type=int, default=0)
     ap.add_argument("--CT", type=int, default=0)
     ap.add_argument("--waves", type=int, default=0)
     args = ap.parse_args()
+    global PROFILING
+    PROFILING = args.profile
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (the product path has no multi-GPU part); "
               "use --gpus 1", file=sys.stderr)
@@ -362,9 +370,10 @@ def main():
                      "kernel_us": head["kernel_us"], "kernel_us_min": head["kernel_us_min"],
                      "algorithmic_bytes": head["algorithmic_bytes"], "t_roof_us": head["t_roof_us"],
                      "mfma_needed": head["mfma_needed"], "mfma_issued": head["mfma_issued"],
-                     "launch_floor_us": launch_floor_us(), "copy_GBs": copy_bandwidth_GBs()},
+                     "launch_floor_us": None if PROFILING else launch_floor_us(),
+                     "copy_GBs": None if PROFILING else copy_bandwidth_GBs()},
     }
-    out["roofline"]["frac_of_copy"] = head["achieved_GBs"] / out["roofline"]["copy_GBs"]
+    out["roofline"]["frac_of_copy"] = None if PROFILING else head["achieved_GBs"] / out["roofline"]["copy_GBs"]
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(cfg, *layer)
     if per:
