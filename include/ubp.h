@@ -242,8 +242,11 @@ int64_t ubp_packed_info(const ubp_packed *p, int32_t what);
  *   which = 1: gather layout (sub_stripes, col_tiles as in ubp_plan).  rg_ptr int32[row groups
  *              + 1] first step record of each row group, rg_order int32[row groups] row groups
  *              by decreasing work, stream uint32[stream_words] the step records.
- *   which = 2: block layout (sub_stripes 2, 4 or 5; col_tiles ignored).  rg_ptr, rg_order as
- *              above, stream = the operand records (256 words per step), meta = 2 words per step.
+ *   which = 2: block layout (sub_stripes 2, 4 or 5; col_tiles ignored).  Row groups are runs of
+ *              1 .. sub_stripes consecutive 16-row stripes (short where many blocks start).
+ *              rg_ptr as above; rg_order int32[2 * row groups + 1]: the row groups by decreasing
+ *              work, then the first stripe of every row group and, last, the number of stripes;
+ *              stream = the operand records (256 words per step), meta = 2 words per step.
  *   which = 3: the dense operand tiles (sub_stripes, col_tiles ignored).  row_groups = number
  *              of 16-row stripes, rg_ptr = rg_order = NULL, stream = [stripes][tiles per
  *              stripe][64 lanes][8] 16-bit weights as 32-bit words (tiles per stripe =

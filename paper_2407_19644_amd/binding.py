@@ -229,7 +229,8 @@ class Packed:
 
     def layout(self, sub_stripes, col_tiles, which=1):
         """ubp_packed_layout, as copies.  which=1 (gather layout): (rg_ptr int32[nrg + 1], rg_order
-        int32[nrg], stream uint32[...]); which=2 (block layout): (rg_ptr, rg_order, records
+        int32[nrg], stream uint32[...]); which=2 (block layout): (rg_ptr, rg_order int32[2 nrg + 1] = the
+        order followed by the first stripe of every row group, records
         uint32[steps + spare][256], meta uint32[steps + spare][2]); which=3 (dense operand tiles):
         (None, None, uint16[stripes][tiles][64][8], occupied uint32[stripes][words])."""
         nrg = ctypes.c_int32(0)
@@ -249,7 +250,8 @@ class Packed:
         if which == 3:
             t = copy(c, words.value, np.uint32).view(np.uint16)
             return None, None, t.reshape(nrg.value, -1, 64, 8), copy(m, mwords.value, np.uint32).reshape(nrg.value, -1)
-        rg_ptr, rg_order = copy(a, nrg.value + 1, np.int32), copy(b, nrg.value, np.int32)
+        rg_ptr = copy(a, nrg.value + 1, np.int32)
+        rg_order = copy(b, nrg.value if which != 2 else 2 * nrg.value + 1, np.int32)
         if which == 2:
             return rg_ptr, rg_order, copy(c, words.value, np.uint32).reshape(-1, 256), copy(m, mwords.value, np.uint32).reshape(-1, 2)
         return rg_ptr, rg_order, copy(c, words.value, np.uint32)

@@ -26,8 +26,9 @@ constexpr int kBlkCT = 4; // 64-pixel column tiles (the ring geometry of CT = 4)
 //    number of chunks whose share it has landed.  Every consumer publishes one counter of its
 //    own, the number of leading chunks it will not read again; a slot is refilled once all of
 //    them have passed the chunk that occupies it.  No workgroup barrier after start-up.
-//  * Each consumer owns one row group (G aligned 16-row stripes) and keeps its G x 4 output
-//    tiles in fp32 accumulators for the whole K loop (output stationary).  Its steps are a
+//  * Each consumer owns one row group (a run of at most G aligned 16-row stripes; runs with many
+//    blocks are shorter, so that the consumers of a workgroup carry similar loads) and keeps its
+//    G x 4 output tiles in fp32 accumulators for the whole K loop (output stationary).  Its steps are a
 //    contiguous run of 1 KB operand records, fetched D steps ahead into a register ring, and of
 //    8-byte metadata words, fetched 64 steps at a time (one per lane) and handed out with
 //    v_readlane: a step costs one vector memory instruction.
@@ -171,6 +172,8 @@ __global__ __launch_bounds__(MAXT) void blk_kernel(BlkArgs a) {
 
     // ------------------------------------------------------------------ consumer
     const int rg = __builtin_amdgcn_readfirstlane(a.rg_order[q]);
+    const int stripe0 = __builtin_amdgcn_readfirstlane(a.rg_order[a.nrg + rg]);          // the group's first stripe
+    const int stripes = __builtin_amdgcn_readfirstlane(a.rg_order[a.nrg + rg + 1]) - stripe0; // at most G
     const int s_first = __builtin_amdgcn_readfirstlane(a.rg_ptr[rg]);
     const int s_all = __builtin_amdgcn_readfirstlane(a.rg_ptr[rg + 1]);
 
@@ -227,8 +230,8 @@ __global__ __launch_bounds__(MAXT) void blk_kernel(BlkArgs a) {
     auto release_upto = [&](int upto) {
         if (upto > released) {
             released = upto;
-            // relaxed + a compiler barrier: the reads of these chunks returned before the MFMAs
-            // that used them were issued, and LDS executes this wavefront's operations in order
+            // relaxed + a compiler barrier: LDS executes this wavefront's operations in order, so
+            // every read issued before this store is served before the store becomes visible
             asm volatile("" ::: "memory");
             if (lane == 0) __hip_atomic_store(mine, (uint32_t)upto, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
         }
@@ -265,7 +268,6 @@ __global__ __launch_bounds__(MAXT) void blk_kernel(BlkArgs a) {
                 const uint32_t m0 = __builtin_amdgcn_readlane(mcur[0], li + d);
                 const uint32_t m1 = __builtin_amdgcn_readlane(mcur[1], li + d);
                 const uint32_t aA = m0 & 0xffffu, aB = m0 >> 16;
-                release_upto((int)(m1 >> 22));
                 wait_published((int)((max(aA, aB) + 15u) >> 6));
                 // ---- gather: the 16 + 16 window rows, four pixel tiles
                 short8v xf[CT];
@@ -284,6 +286,9 @@ __global__ __launch_bounds__(MAXT) void blk_kernel(BlkArgs a) {
                         xf[c] = __builtin_shufflevector(p0, p1, 0, 1, 2, 3, 4, 5, 6, 7);
                     }
                 }
+                // hand back the chunks that no later step reads: LDS executes this wavefront's
+                // operations in order, so the reads above are served before the counter moves
+                release_upto((int)(m1 >> 22));
                 // ---- the operand's two parts: rows n >= o stay in the stripe the block starts in
                 const uint32_t oA = m1 & 15u, oB = (m1 >> 4) & 15u;
                 const uint4v f = wf[d];
@@ -317,7 +322,7 @@ __global__ __launch_bounds__(MAXT) void blk_kernel(BlkArgs a) {
     if (broken && lane == 0) atomicOr(a.err, 2u);
 
     // ---- store: lane (g = lane/16, n = lane%16) holds pixels col0 + 16*c + 4*g + v of row
-    // 16*(G*rg + j) + n.  Rows no block touches are stored as zeros like any other.
+    // 16*(stripe0 + j) + n, j < stripes.  Rows no block touches are stored as zeros like any other.
     TY *Yt = static_cast<TY *>(a.Y);
     if constexpr (sizeof(TY) == 2) {
         if (a.out_bytes != 0) {
@@ -332,6 +337,7 @@ __global__ __launch_bounds__(MAXT) void blk_kernel(BlkArgs a) {
             char *scratch = smem + a.ring_bytes + 32 * sizeof(uint32_t) + wave * a.out_bytes;
 #pragma unroll
             for (int j = 0; j < G; ++j) {
+                if (j >= stripes) break;
 #pragma unroll
                 for (int c = 0; c < CT; ++c) {
                     typedef TY ty4 __attribute__((ext_vector_type(4)));
@@ -345,7 +351,7 @@ __global__ __launch_bounds__(MAXT) void blk_kernel(BlkArgs a) {
                 for (int i = 0; i < NI; ++i) {
                     const int r = i * (64 / PR) + lane / PR, lp = lane % PR;
                     const uint4v o = *reinterpret_cast<const uint4v *>(scratch + r * RB + ((lp ^ ((r / RP) & (PR - 1))) << 4));
-                    const int row = (rg * G + j) * kStripe + r;
+                    const int row = (stripe0 + j) * kStripe + r;
                     if (row < a.M) *reinterpret_cast<uint4v *>(Yt + (int64_t)row * a.ldy + col0 + lp * 8) = o;
                 }
             }
@@ -354,8 +360,8 @@ __global__ __launch_bounds__(MAXT) void blk_kernel(BlkArgs a) {
     }
 #pragma unroll
     for (int j = 0; j < G; ++j) {
-        const int row = (rg * G + j) * kStripe + n;
-        if (row >= a.M) continue;
+        const int row = (stripe0 + j) * kStripe + n;
+        if (j >= stripes || row >= a.M) continue;
 #pragma unroll
         for (int c = 0; c < CT; ++c) {
             const int px = col0 + 16 * c + 4 * g;

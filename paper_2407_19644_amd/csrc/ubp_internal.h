@@ -78,9 +78,10 @@ struct StripeLayout {
 // Host image of the block kernel's layout (blocks of at most 16 rows; column tiles of 64 pixels,
 // i.e. the ring geometry of CT = 4), for G stripes per wavefront.
 //
+// Row groups are consecutive runs of at most G aligned 16-row stripes, cut so that runs with many
+// blocks are short (a workgroup lasts as long as its heaviest row group).
 // A block is cut into "halves" of 16 consecutive columns (a block at most 16 wide is one half).
-// For a row group of 16*G aligned rows every half of every block that has a row in the group
-// is an incidence.  The X rows of a half are the window [a, a + 16), a = its first column
+// For a row group every half of every block that has a row in the group is an incidence.  The X rows of a half are the window [a, a + 16), a = its first column
 // (moved left where the window would pass the last row of X).  A step = two halves (A, B) whose
 // blocks start in the same stripe of the row group, or one half and nothing.
 //   meta : 2 dwords per step
@@ -90,8 +91,8 @@ struct StripeLayout {
 //                            0 when they start in the stripe above the group, 15 for an empty step
 //            bit 12 / 13     some half has rows in stripe jj - 1 ("lower part", rows n >= o) /
 //                            in stripe jj ("upper part", rows n < o)
-//            bits 22-31      number of leading 64-row chunks of X that no step from the one
-//                            before this on reads
+//            bits 22-31      number of leading 64-row chunks of X that no later step reads
+//                            (handed back as soon as this step's reads are issued)
 //   frags: 256 dwords per step, the MFMA operand of both halves: lane 16 g + n holds, as 16-bit
 //          element e (0..3: half A, 4..7: half B), the weight that row-slot n of the block
 //          (the block row congruent to n modulo 16: the paper's rotation, Section 4.2, with
@@ -103,7 +104,9 @@ struct BlkLayout {
     int G = 0;
     bool built = false;
     int nrg = 0, nch = 0;
-    std::vector<int32_t> rg_ptr, rg_order;
+    std::vector<int32_t> rg_ptr;    // [nrg + 1] first step of each row group
+    std::vector<int32_t> rg_order;  // [nrg] row groups, heaviest first, then [nrg + 1] the first stripe of each row group
+    std::vector<int32_t> rg_first;  // the second part of rg_order while the layout is built
     std::vector<uint32_t> meta, frags;
     int64_t nsteps = 0;
     int64_t total_mfma = 0;   // MFMA issues per 16-column tile

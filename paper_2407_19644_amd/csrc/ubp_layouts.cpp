@@ -244,14 +244,77 @@ struct Half {
     bool hi;        // has rows in the stripe after the one it starts in (inside the row group)
 };
 
+// Row groups of the block layout: consecutive runs of at most G stripes.  A run costs roughly
+// (halves that start in it + halves that reach into it from the stripe above) / 2 steps, and a
+// workgroup lasts as long as its heaviest row group, so stripes with many blocks get short runs
+// and the others long ones.  The number of runs is the smallest possible, rounded up to a whole
+// number of workgroup rows of kBlkConsumers wavefronts (the spare runs cost nothing there); the
+// cut minimises the sum of cubed costs.  first[g] = first stripe of run g, first[runs] = nstripes.
+constexpr int kBlkConsumers = 14;
+
+std::vector<int32_t> cut_row_groups(const ubp_packed *p, int G) {
+    const int M = p->M, bh = p->bh;
+    const int nstripes = (M + kStripe - 1) / kStripe;
+    const int nh = (p->bw + 15) / 16;
+    std::vector<int64_t> start((size_t)nstripes + 1, 0), reach((size_t)nstripes + 1, 0); // halves starting in / reaching below stripe s
+    for (int i = 0; i + bh <= M; ++i) {
+        const int64_t nb = p->indptr[(size_t)i + 1] - p->indptr[(size_t)i];
+        start[(size_t)(i / kStripe)] += nb * nh;
+        if (i % kStripe + bh > kStripe) reach[(size_t)(i / kStripe)] += nb * nh;
+    }
+    const int least = (nstripes + G - 1) / G;
+    int runs = std::min(nstripes, (least + kBlkConsumers - 1) / kBlkConsumers * kBlkConsumers);
+    std::vector<int32_t> first;
+    auto fixed = [&]() {
+        first.clear();
+        for (int s = 0; s < nstripes; s += G) first.push_back(s);
+        first.push_back(nstripes);
+    };
+    if (runs == least || (int64_t)runs * nstripes > (int64_t(1) << 24)) {
+        fixed();
+        return first;
+    }
+    auto cost = [&](int s0, int s1) { // stripes s0 .. s1 - 1
+        int64_t c = s0 > 0 ? (reach[(size_t)s0 - 1] + 1) / 2 : 0;
+        for (int s = s0; s < s1; ++s) c += (start[(size_t)s] + 1) / 2;
+        return (double)c * (double)c * (double)c;
+    };
+    const double kInf = 1e300;
+    // best[k][s]: stripes [0, s) in k runs
+    std::vector<std::vector<double>> best((size_t)runs + 1, std::vector<double>((size_t)nstripes + 1, kInf));
+    std::vector<std::vector<int8_t>> len((size_t)runs + 1, std::vector<int8_t>((size_t)nstripes + 1, 0));
+    best[0][0] = 0.0;
+    for (int k = 1; k <= runs; ++k)
+        for (int s = 1; s <= nstripes; ++s)
+            for (int l = 1; l <= G && l <= s; ++l) {
+                const double b = best[(size_t)k - 1][(size_t)(s - l)];
+                if (b >= kInf) continue;
+                const double c = b + cost(s - l, s);
+                if (c < best[(size_t)k][(size_t)s]) {
+                    best[(size_t)k][(size_t)s] = c;
+                    len[(size_t)k][(size_t)s] = (int8_t)l;
+                }
+            }
+    if (best[(size_t)runs][(size_t)nstripes] >= kInf) {
+        fixed();
+        return first;
+    }
+    first.assign((size_t)runs + 1, 0);
+    for (int k = runs, s = nstripes; k >= 1; --k) {
+        first[(size_t)k] = s;
+        s -= len[(size_t)k][(size_t)s];
+    }
+    return first;
+}
+
 void build_blk(const ubp_packed *p, BlkLayout &L, int G) {
     const int M = p->M, K = p->K, bh = p->bh, bw = p->bw;
     constexpr int CT = 4;
     const int R = ring_slots(CT);
     const int pair_span = R / 2 - 2; // chunks two halves of a step may lie apart
-    const int rgh = kStripe * G;
     L.G = G;
-    L.nrg = (M + rgh - 1) / rgh;
+    L.rg_first = cut_row_groups(p, G);
+    L.nrg = (int)L.rg_first.size() - 1;
     L.nch = (K + kSlotRows - 1) / kSlotRows;
     L.rg_ptr.assign((size_t)L.nrg + 1, 0);
     L.meta.clear();
@@ -269,16 +332,17 @@ void build_blk(const ubp_packed *p, BlkLayout &L, int G) {
     std::vector<int> cls[kStripe + 1];
 
     for (int rg = 0; rg < L.nrg; ++rg) {
-        const int row0 = rg * rgh, row1 = std::min(M, row0 + rgh);
+        const int row0 = kStripe * L.rg_first[(size_t)rg], row1 = std::min(M, kStripe * L.rg_first[(size_t)rg + 1]);
+        const int cnt = L.rg_first[(size_t)rg + 1] - L.rg_first[(size_t)rg]; // stripes of this run (at most G)
         halves.clear();
         for (int j = 0; j <= G; ++j) cls[j].clear();
         const int s0 = std::max(0, row0 - bh + 1), s1 = std::min(nstart, row1);
         for (int i = s0; i < s1; ++i)
             for (int32_t b = p->indptr[(size_t)i]; b < p->indptr[(size_t)i + 1]; ++b) {
-                const int t = i - row0;                      // -15 .. rgh - 1
+                const int t = i - row0;                      // -15 .. row1 - row0 - 1
                 const int j = t >= 0 ? t / kStripe : -1;     // stripe of the row group the block starts in
                 const int o = ((t % kStripe) + kStripe) % kStripe;
-                const bool hi = o + bh > kStripe && j + 1 < G && row0 + kStripe * (j + 1) < row1;
+                const bool hi = o + bh > kStripe && j + 1 < cnt && row0 + kStripe * (j + 1) < row1;
                 if (j < 0 && !hi) continue;                  // no row inside the group
                 for (int h = 0; h < nh; ++h) {
                     const int a = std::min(p->indices[(size_t)b] + 16 * h, K - 16);
@@ -318,14 +382,16 @@ void build_blk(const ubp_packed *p, BlkLayout &L, int G) {
             }
         };
         set_rel(real);
-        // When a step's gather is issued the wavefront holds every chunk from rel(t-1) to
-        // cmax(t); two of the R ring slots must stay free, or producer and consumers could wait
-        // for each other.  Where two neighbouring steps lie further apart an empty step goes
-        // between them: it reads nothing, and rel(empty) = rel(t).
+        // A wavefront hands back, right after the reads of step t - 1, every chunk below rel(t);
+        // while it waits for the chunks of step t it therefore holds rel(t) .. cmax(t), which is
+        // at most pair_span + 2 chunks: the ring always has free slots for the producers.
         steps.clear();
         const Step empty{-1, -1, 15, 0, 0, 0};
         for (size_t t = 0; t < real.size(); ++t) {
-            if (t > 0 && real[t].cmax - real[t - 1].rel > R - 2) steps.push_back(empty);
+            if (real[t].cmax - real[t].rel > R - 2) { // (cannot happen: see pair_span)
+                L.G = 0;
+                return;
+            }
             steps.push_back(real[t]);
         }
         while (steps.size() % kPrefetchDepth != 0) steps.push_back(empty);
@@ -337,7 +403,7 @@ void build_blk(const ubp_packed *p, BlkLayout &L, int G) {
             const size_t mpos = L.meta.size(), fpos = L.frags.size();
             L.meta.resize(mpos + 2, 0u);
             L.frags.resize(fpos + 256, 0u);
-            const uint32_t rel = (uint32_t)steps[si > 0 ? si - 1 : 0].rel;
+            const uint32_t rel = (uint32_t)(si + 1 < steps.size() ? steps[si + 1].rel : L.nch); // after this step's reads
             if (st.jj == 15) {
                 L.meta[mpos + 1] = (15u << 8) | (rel << 22);
                 ++L.nsteps;
@@ -383,6 +449,7 @@ void build_blk(const ubp_packed *p, BlkLayout &L, int G) {
     std::iota(L.rg_order.begin(), L.rg_order.end(), 0);
     std::stable_sort(L.rg_order.begin(), L.rg_order.end(),
                      [&](int32_t a, int32_t b) { return rg_weight[(size_t)a] > rg_weight[(size_t)b]; });
+    L.rg_order.insert(L.rg_order.end(), L.rg_first.begin(), L.rg_first.end());
 }
 
 } // namespace

@@ -239,17 +239,23 @@ def _decode_block_layout(packed, G, M, K):
     n >= o: the stripe the block starts in, rows n < o: the next one), the chunks a step needs
     against the chunks handed back.  Returns the dense matrix (16-bit patterns) and the MFMA count."""
     rg_ptr, rg_order, recs, meta = packed.layout(G, 0, 2)
-    nrg = len(rg_order)
+    nrg = len(rg_ptr) - 1
+    rg_order, first = rg_order[:nrg], rg_order[nrg:]                # order, then the first stripe of every row group
     assert sorted(rg_order.tolist()) == list(range(nrg))
+    nstripes = -(-M // 16)
+    assert len(first) == nrg + 1 and first[0] == 0 and first[-1] == nstripes
+    assert (np.diff(first) >= 1).all() and (np.diff(first) <= G).all()  # consecutive runs of 1 .. G stripes
+    assert nrg == min(nstripes, -(-(-(-nstripes // G)) // 14) * 14)     # fewest runs, rounded up to whole workgroup rows
     nsteps = int(rg_ptr[-1])
     assert recs.shape == (nsteps + 4, 256) and meta.shape == (nsteps + 128, 2)
     assert not recs[nsteps:].any() and not meta[nsteps:].any()
     R, nch = 16, -(-K // 64)
     lanes = np.arange(64)
     g, n = lanes // 16, lanes % 16
-    Wd = np.zeros((nrg * 16 * G, K), dtype=np.uint16)
+    Wd = np.zeros((nstripes * 16, K), dtype=np.uint16)
     mfma = 0
     for rg in range(nrg):
+        cnt = int(first[rg + 1] - first[rg])
         assert (rg_ptr[rg + 1] - rg_ptr[rg]) % 4 == 0
         prev_rel = 0
         for s in range(rg_ptr[rg], rg_ptr[rg + 1]):
@@ -258,15 +264,19 @@ def _decode_block_layout(packed, G, M, K):
             o = (m1 & 15, (m1 >> 4) & 15)
             jj, do_lo, do_hi, rel = (m1 >> 8) & 15, (m1 >> 12) & 1, (m1 >> 13) & 1, m1 >> 22
             assert (m1 >> 14) & 0xff == 0
+            # rel is handed back after this step's reads: no later step may read below it, and
+            # what the wavefront still holds while it waits for this step's chunks fits the ring
             assert prev_rel <= rel <= nch
-            prev_rel = rel
+            held_from, prev_rel = prev_rel, rel
+            if s == rg_ptr[rg + 1] - 1:
+                assert rel == nch
             frag = recs[s].view(np.uint16).reshape(64, 8)
             if jj == 15:
                 assert m0 == 0 and not frag.any() and not do_lo and not do_hi
                 continue
-            assert jj <= G and do_lo == (jj >= 1) and (do_lo or do_hi)
+            assert jj <= cnt and do_lo == (jj >= 1) and (do_lo or do_hi)
             need = (max(a) + 15) >> 6
-            assert rel <= min(a) >> 6 and need < nch and need - rel <= R - 2
+            assert held_from <= min(a) >> 6 and need < nch and need - held_from <= R - 2
             assert max(a) + 16 <= K
             mfma += do_lo + do_hi
             for e in range(8):
@@ -277,9 +287,11 @@ def _decode_block_layout(packed, G, M, K):
                 lower = n >= o[h]                                      # rows that stay in stripe jj - 1
                 for part, stripe, on in ((lower, jj - 1, do_lo), (~lower, jj, do_hi)):
                     sel = part & (v != 0)
-                    if not on or not 0 <= stripe < G:
+                    if not on:
+                        assert not sel.any() or not 0 <= stripe < cnt     # (weights of a part that is off belong to a neighbour)
                         continue
-                    rows = (rg * G + stripe) * 16 + n[sel]
+                    assert 0 <= stripe < cnt
+                    rows = (int(first[rg]) + stripe) * 16 + n[sel]
                     assert not Wd[rows, rho[sel]].any()                # no weight is delivered twice
                     Wd[rows, rho[sel]] = v[sel]
     assert not Wd[M:].any()
