@@ -167,7 +167,12 @@ __global__ __launch_bounds__(MAXT) void blk_kernel(BlkArgs a) {
         publish_upto(a.nch);
         return;
     }
-    const int q = wgrow * NC + wave;
+    // Wavefront w runs on SIMD w mod 4 (in some order), and the producers, the last NP wavefronts,
+    // take little of theirs: the SIMDs that host a producer have one consumer fewer and get the
+    // workgroup's heaviest row groups (rg_order is sorted by decreasing work).
+    int pos = wave;
+    if (NP == 2 && NC == 14) pos = (wave & 2) ? (wave >> 2) * 2 + (wave & 1) : 6 + (wave >> 2) * 2 + (wave & 1);
+    const int q = wgrow * NC + pos;
     if (q >= a.nrg) return; // no row group for this wavefront
 
     // ------------------------------------------------------------------ consumer
@@ -208,7 +213,7 @@ __global__ __launch_bounds__(MAXT) void blk_kernel(BlkArgs a) {
     int released = 0;   // chunks this wavefront has handed back
     int ready_upto = 0; // chunks known to be resident
     bool broken = false;
-    uint32_t *mine = released_p + wave;
+    uint32_t *mine = released_p + pos; // (the producers look at positions 0 .. active - 1)
     auto wait_published = [&](int chunk) {
         if (chunk < ready_upto) return;
         int spins = 0;
