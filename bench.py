@@ -65,7 +65,7 @@ def timed_replays(run_once, stream, est_ms):
     return wall, [e0.elapsed_time(e1) for e0, e1 in ev]
 
 
-def measure(cfg, layer, steps, warmup, y_dtype, plan_kw, use_graph, hot, verify_rows=0):
+def measure(cfg, layer, steps, warmup, y_dtype, plan_kw, use_graph, hot, verify_rows=0, fused=False):
     import torch
     import paper_2407_19644_amd as ubp
 
@@ -97,9 +97,18 @@ def measure(cfg, layer, steps, warmup, y_dtype, plan_kw, use_graph, hot, verify_
     for s in range(nsets):
         chosen = ubp.spmm_prepare(Ps[s], Xs[s].data_ptr(), N, N, Ys[s].data_ptr(), N, y_dtype, plan)
 
+    bias = None
+    if fused:                              # bias per output row + ReLU, fused into the stores
+        bias = (np.random.default_rng(5).standard_normal(cfg.M) * 0.1).astype(np.float32)
+        bias_d = torch.from_numpy(bias).cuda()
+
     def step(i, stream):
         s = i % nsets
-        ubp.spmm(Ps[s], Xs[s].data_ptr(), N, N, Ys[s].data_ptr(), N, y_dtype, stream, plan)
+        if fused:
+            ubp.spmm_fused(Ps[s], Xs[s].data_ptr(), N, N, Ys[s].data_ptr(), N, y_dtype, bias_d.data_ptr(), "relu", 0.0, 0.0,
+                           stream, plan)
+        else:
+            ubp.spmm(Ps[s], Xs[s].data_ptr(), N, N, Ys[s].data_ptr(), N, y_dtype, stream, plan)
 
     stream = torch.cuda.Stream()          # default priority; every launch and event is on it
     with torch.cuda.stream(stream):
@@ -135,7 +144,7 @@ def measure(cfg, layer, steps, warmup, y_dtype, plan_kw, use_graph, hot, verify_
         raise RuntimeError("%s: a bounded wait inside a kernel ran out (flags %s): the timing is void" % (cfg.name, flags))
     checked = 0
     if verify_rows:
-        checked = verify(cfg, layer, Ys[(warmup + steps - 1) % nsets], y_dtype, verify_rows)
+        checked = verify(cfg, layer, Ys[(warmup + steps - 1) % nsets], y_dtype, verify_rows, bias)
 
     issued = {2: 100 + ubp.layout_slot(chosen.sub_stripes, chosen.col_tiles) if chosen.kernel == 2 else -1,
               4: 10, 5: 10, 6: 300 + {2: 0, 4: 1, 5: 2}.get(chosen.sub_stripes, 1)}.get(chosen.kernel, -1)
@@ -163,7 +172,7 @@ def measure(cfg, layer, steps, warmup, y_dtype, plan_kw, use_graph, hot, verify_
     return res
 
 
-def verify(cfg, layer, Yt, y_dtype, nrows):
+def verify(cfg, layer, Yt, y_dtype, nrows, bias=None):
     """Rows of the timed run's last Y against the oracle (first, last, stripe borders and a seeded
     draw); raises on a mismatch.  Tolerances as in the parity tests."""
     import torch
@@ -173,6 +182,8 @@ def verify(cfg, layer, Yt, y_dtype, nrows):
     rng = np.random.default_rng(7)
     rows = sorted(set([0, 15, 16, cfg.M - 16, cfg.M - 1]) | set(int(r) for r in rng.integers(0, cfg.M, size=max(0, nrows - 5))))
     Yref = oracle.spmm(decode_f64(W, cfg.dtype), cfg.bh, cfg.bw, blocks, decode_f64(X, cfg.dtype), rows=rows)
+    if bias is not None:
+        Yref = oracle.fused(Yref, bias.astype(np.float64), "relu", rows=rows)
     t = Yt[torch.tensor(rows, device=Yt.device)].detach().cpu()
     Y = decode_f64(t.view(torch.uint16).numpy(), "bf16") if y_dtype == "bf16" else t.numpy().astype(np.float64)
     if not np.isfinite(Y).all():
@@ -373,6 +384,10 @@ def main():
                      "launch_floor_us": None if PROFILING else launch_floor_us(),
                      "copy_GBs": None if PROFILING else copy_bandwidth_GBs()},
     }
+    if not args.only:
+        fe = measure(cfg, layer, args.steps, args.warmup, args.y_dtype, plan_kw, use_graph, args.hot, verify_rows=8, fused=True)
+        out["fused_epilogue"] = {"what": "ubp_spmm_fused on the headline layer: bias per output row + ReLU in the stores",
+                                 "kernel_us": fe["kernel_us"], "over_plain": fe["kernel_us"] / head["kernel_us"]}
     out["roofline"]["frac_of_copy"] = None if PROFILING else head["achieved_GBs"] / out["roofline"]["copy_GBs"]
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(cfg, *layer)

@@ -193,6 +193,28 @@ ubp_status ubp_spmm_plan(const ubp_packed *p, const void *X_dev, int64_t ldx, in
                          const ubp_plan *plan);
 
 /*
+ * The product with a fused epilogue, for callers that would otherwise run a second pass over Y
+ * (a pruned convolution is followed by its bias and its activation):
+ *     Y[i][j] = act( sum_k W[i][k] X[k][j] + bias[i] ),
+ * bias added to the fp32 accumulator and the activation applied in fp32 before the one rounding
+ * to y_dtype.  All kernels support it; nothing else about the call changes.
+ *   bias_dev   : DEVICE pointer to M floats (one per output channel / row of Y), or NULL (no bias).
+ *   activation : 0 none; 1 ReLU, max(v, 0); 2 clamp to [lo, hi] (requires lo <= hi, else
+ *                UBP_ERR_INVALID_ARG).  max / min are IEEE maxNum / minNum: a NaN becomes the
+ *                lower bound.  lo / hi are ignored for 0 and 1.
+ * epilogue == NULL, or no bias and activation 0, is ubp_spmm / ubp_spmm_plan; plan may be NULL.
+ */
+typedef struct {
+    const float *bias_dev;
+    int32_t activation;
+    float lo, hi;
+} ubp_epilogue;
+
+ubp_status ubp_spmm_fused(const ubp_packed *p, const void *X_dev, int64_t ldx, int32_t N,
+                          void *Y_dev, int64_t ldy, ubp_dtype y_dtype, const ubp_epilogue *epilogue,
+                          void *hip_stream, const ubp_plan *plan);
+
+/*
  * Everything ubp_spmm_plan does with these arguments except the launch: resolves the kernel
  * and its shape, builds and uploads the re-layout of W that shape reads (host and device
  * allocation, synchronous copies) and raises the kernel's LDS limit.  X_dev and Y_dev are only

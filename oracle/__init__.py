@@ -115,3 +115,25 @@ def pack(W_enc, bh, bw, blocks):
     if rc:
         raise OracleError(rc)
     return indptr, indices, values
+
+
+def fused(Y64, bias=None, activation=None, lo=0.0, hi=0.0, rows=None):
+    """The epilogue of a pruned convolution applied to the exact product, in float64:
+    act(Y[i][j] + bias[i]) with act = identity (None), max(v, 0) ("relu") or min(max(v, lo), hi)
+    ("clamp"); max / min ignore a NaN operand, so a NaN becomes the lower bound.  `rows`: the
+    output rows Y64 holds when it is not the whole of Y (then bias[rows] is added)."""
+    Y = np.array(Y64, dtype=np.float64)
+    if bias is not None:
+        b = np.asarray(bias, dtype=np.float64)
+        if rows is not None:
+            b = b[np.asarray(rows)]
+        Y = Y + b[:, None]
+    if activation in (None, "none"):
+        return Y
+    if activation == "relu":
+        return np.fmax(Y, 0.0)
+    if activation == "clamp":
+        if not lo <= hi:
+            raise ValueError("clamp needs lo <= hi")
+        return np.fmin(np.fmax(Y, lo), hi)
+    raise ValueError(activation)

@@ -25,7 +25,9 @@ EXPORTS = ("ubp_target_block_count", "ubp_select_reference", "ubp_pack", "ubp_pa
            "ubp_packed_indices", "ubp_packed_values", "ubp_spmm", "ubp_spmm_plan", "ubp_packed_info",
            "ubp_packed_free", "ubp_status_string", "ubp_packed_device_error", "ubp_packed_layout",
            "ubp_spmm_prepare", "ubp_launch_floor", "ubp_block_scores", "ubp_select_greedy", "ubp_select_bed",
-           "ubp_select_optimal", "ubp_selection_to_blocks", "ubp_select_blocks", "ubp_selection_efficacy")
+           "ubp_select_optimal", "ubp_selection_to_blocks", "ubp_select_blocks", "ubp_selection_efficacy",
+           "ubp_spmm_fused")
+ACTIVATIONS = {None: 0, "none": 0, "relu": 1, "clamp": 2}
 SELECT_METHODS = {"greedy": 0, "bed": 1, "optimal": 2}
 
 
@@ -40,6 +42,11 @@ class Plan(ctypes.Structure):
     _fields_ = [("kernel", ctypes.c_int32), ("sub_stripes", ctypes.c_int32), ("col_tiles", ctypes.c_int32),
                 ("waves", ctypes.c_int32), ("rows_per_range", ctypes.c_int32), ("producers", ctypes.c_int32),
                 ("wg_rows", ctypes.c_int32)]
+
+
+class Epilogue(ctypes.Structure):
+    """Mirror of ubp_epilogue."""
+    _fields_ = [("bias_dev", ctypes.c_void_p), ("activation", ctypes.c_int32), ("lo", ctypes.c_float), ("hi", ctypes.c_float)]
 
 
 _lib = None
@@ -81,6 +88,8 @@ def load_library():
     L.ubp_packed_layout.restype = ctypes.c_int
     L.ubp_spmm_prepare.argtypes = [vp, vp, i64, i32, vp, i64, ctypes.c_int, ctypes.POINTER(Plan), ctypes.POINTER(Plan)]
     L.ubp_spmm_prepare.restype = ctypes.c_int
+    L.ubp_spmm_fused.argtypes = [vp, vp, i64, i32, vp, i64, ctypes.c_int, ctypes.POINTER(Epilogue), vp, ctypes.POINTER(Plan)]
+    L.ubp_spmm_fused.restype = ctypes.c_int
     L.ubp_launch_floor.argtypes = [vp]
     L.ubp_launch_floor.restype = ctypes.c_int
     L.ubp_block_scores.argtypes = [vp, ctypes.c_int, i64, i32, i32, i32, i32, i32, vp, i64]
@@ -321,6 +330,17 @@ def spmm(packed, X_ptr, ldx, N, Y_ptr, ldy, y_dtype, stream=0, plan=None):
         rc = L.ubp_spmm_plan(packed.handle, X_ptr, ldx, N, Y_ptr, ldy, DTYPES[y_dtype], stream, ctypes.byref(plan))
     if rc != UBP_OK:
         raise UBPError(rc, "ubp_spmm")
+
+
+def spmm_fused(packed, X_ptr, ldx, N, Y_ptr, ldy, y_dtype, bias_ptr=None, activation=None, lo=0.0, hi=0.0, stream=0,
+               plan=None):
+    """ubp_spmm_fused with raw DEVICE pointers; bias_ptr: M floats on the device or None;
+    activation: None / "relu" / "clamp" (with lo, hi)."""
+    ep = Epilogue(bias_ptr, ACTIVATIONS[activation], float(lo), float(hi))
+    rc = load_library().ubp_spmm_fused(packed.handle, X_ptr, ldx, N, Y_ptr, ldy, DTYPES[y_dtype], ctypes.byref(ep), stream,
+                                       ctypes.byref(plan) if plan is not None else None)
+    if rc != UBP_OK:
+        raise UBPError(rc, "ubp_spmm_fused")
 
 
 def spmm_prepare(packed, X_ptr, ldx, N, Y_ptr, ldy, y_dtype, plan=None):

@@ -418,7 +418,7 @@ ubp_status resolve(const ubp_packed *p, int N, int64_t ldx_bytes, bool vec_ok, c
 }
 
 StripeArgs stripe_args(const ubp_packed *p, const Shape &s, const void *X, int64_t ldx, int N, void *Y, int64_t ldy, bool vec_ok,
-                       int ctile0) {
+                       int ctile0, const Epilogue &ep) {
     const int slot = layout_slot(s.G, s.CT);
     const StripeLayout &L = p->sg[slot];
     const StripeLayoutDev &LD = p->d_sg[slot];
@@ -445,13 +445,23 @@ StripeArgs stripe_args(const ubp_packed *p, const Shape &s, const void *X, int64
     a.n_producers = s.NP;
     a.resident = s.resident ? 1 : 0;
     a.vec_ok = vec_ok;
+    a.ep = ep;
     return a;
 }
 
 // The whole of ubp_spmm_plan / ubp_spmm_prepare.  dry: everything but the launch.
 ubp_status execute(const ubp_packed *p, const void *X_dev, int64_t ldx, int32_t N, void *Y_dev, int64_t ldy, ubp_dtype y_dtype,
-                   void *stream, const ubp_plan *plan, bool dry, ubp_plan *chosen) {
+                   void *stream, const ubp_plan *plan, bool dry, ubp_plan *chosen, const ubp_epilogue *fused) {
     if (!p || N < 0) return UBP_ERR_INVALID_ARG;
+    Epilogue ep = {nullptr, 0, 0.f, 0.f};
+    if (fused) {
+        if (fused->activation < 0 || fused->activation > 2) return UBP_ERR_INVALID_ARG;
+        if (fused->activation == 2 && !(fused->lo <= fused->hi)) return UBP_ERR_INVALID_ARG; // (also refuses NaN bounds)
+        ep.bias = fused->bias_dev;
+        ep.on = (fused->bias_dev != nullptr || fused->activation != 0) ? 1 : 0;
+        ep.lo = fused->activation == 1 ? 0.f : fused->activation == 2 ? fused->lo : -INFINITY;
+        ep.hi = fused->activation == 2 ? fused->hi : INFINITY;
+    }
     if (p->device == UBP_HOST_ONLY) return UBP_ERR_INVALID_ARG;
     if (y_dtype != UBP_F32 && y_dtype != p->dtype) return UBP_ERR_INVALID_ARG;
     if (N == 0) return UBP_OK;
@@ -510,8 +520,8 @@ ubp_status execute(const ubp_packed *p, const void *X_dev, int64_t ldx, int32_t 
 
     switch (s.kernel) {
     case 1:
-    case 3: return launch_wros(p, X_dev, ldx, N, Y_dev, ldy, y_dtype, s.rpr, s.kernel == 3, stream, dry);
-    case 2: return launch_stripe(stripe_args(p, s, X_dev, ldx, N, Y_dev, ldy, vec_ok, 0), bf16, y_f32, s.G, s.CT, s.waves, stream, dry);
+    case 3: return launch_wros(p, X_dev, ldx, N, Y_dev, ldy, y_dtype, s.rpr, s.kernel == 3, ep, stream, dry);
+    case 2: return launch_stripe(stripe_args(p, s, X_dev, ldx, N, Y_dev, ldy, vec_ok, 0, ep), bf16, y_f32, s.G, s.CT, s.waves, stream, dry);
     case 4:
     case 5:
     case 7: {
@@ -528,6 +538,7 @@ ubp_status execute(const ubp_packed *p, const void *X_dev, int64_t ldx, int32_t 
         a.N = N;
         a.nstripes = T.nstripes;
         a.err = p->d_error;
+        a.ep = ep;
         a.kt_total = T.kt_pad;
         a.skip = T.tiles_nonzero != (int64_t)T.nstripes * ((p->K + kStep - 1) / kStep) ? 1 : 0; // (padding tiles aside)
         a.n_blocks = (N + 16 * s.CT - 1) / (16 * s.CT);
@@ -563,9 +574,10 @@ ubp_status execute(const ubp_packed *p, const void *X_dev, int64_t ldx, int32_t 
         a.n_producers = s.NP;
         a.out_bytes = 0; // set per launch
         a.err = p->d_error;
+        a.ep = ep;
         ubp_status rc = launch_blk(a, bf16, y_f32, s.G, s.waves, stream, dry);
         if (rc == UBP_OK && has_tail)
-            rc = launch_stripe(stripe_args(p, tail, X_dev, ldx, N, Y_dev, ldy, vec_ok, N / 64), bf16, y_f32, tail.G, tail.CT,
+            rc = launch_stripe(stripe_args(p, tail, X_dev, ldx, N, Y_dev, ldy, vec_ok, N / 64, ep), bf16, y_f32, tail.G, tail.CT,
                                tail.waves, stream, dry);
         return rc;
     }
@@ -582,17 +594,22 @@ extern "C" {
 
 ubp_status ubp_spmm_plan(const ubp_packed *p, const void *X_dev, int64_t ldx, int32_t N, void *Y_dev, int64_t ldy,
                          ubp_dtype y_dtype, void *hip_stream, const ubp_plan *plan) {
-    return ubp::execute(p, X_dev, ldx, N, Y_dev, ldy, y_dtype, hip_stream, plan, false, nullptr);
+    return ubp::execute(p, X_dev, ldx, N, Y_dev, ldy, y_dtype, hip_stream, plan, false, nullptr, nullptr);
 }
 
 ubp_status ubp_spmm(const ubp_packed *p, const void *X_dev, int64_t ldx, int32_t N, void *Y_dev, int64_t ldy,
                     ubp_dtype y_dtype, void *hip_stream) {
-    return ubp::execute(p, X_dev, ldx, N, Y_dev, ldy, y_dtype, hip_stream, nullptr, false, nullptr);
+    return ubp::execute(p, X_dev, ldx, N, Y_dev, ldy, y_dtype, hip_stream, nullptr, false, nullptr, nullptr);
+}
+
+ubp_status ubp_spmm_fused(const ubp_packed *p, const void *X_dev, int64_t ldx, int32_t N, void *Y_dev, int64_t ldy,
+                          ubp_dtype y_dtype, const ubp_epilogue *epilogue, void *hip_stream, const ubp_plan *plan) {
+    return ubp::execute(p, X_dev, ldx, N, Y_dev, ldy, y_dtype, hip_stream, plan, false, nullptr, epilogue);
 }
 
 ubp_status ubp_spmm_prepare(const ubp_packed *p, const void *X_dev, int64_t ldx, int32_t N, void *Y_dev, int64_t ldy,
                             ubp_dtype y_dtype, const ubp_plan *plan, ubp_plan *chosen) {
-    return ubp::execute(p, X_dev, ldx, N, Y_dev, ldy, y_dtype, nullptr, plan, true, chosen);
+    return ubp::execute(p, X_dev, ldx, N, Y_dev, ldy, y_dtype, nullptr, plan, true, chosen, nullptr);
 }
 
 ubp_status ubp_packed_device_error(const ubp_packed *p, uint32_t *flags) {

@@ -329,6 +329,14 @@ __global__ __launch_bounds__(MAXT) void blk_kernel(BlkArgs a) {
     // ---- store: lane (g = lane/16, n = lane%16) holds pixels col0 + 16*c + 4*g + v of row
     // 16*(stripe0 + j) + n, j < stripes.  Rows no block touches are stored as zeros like any other.
     TY *Yt = static_cast<TY *>(a.Y);
+    if (a.ep.on) {
+#pragma unroll
+        for (int j = 0; j < G; ++j) {
+            const float b = epilogue_bias(a.ep, (stripe0 + j) * kStripe + n, a.M);
+#pragma unroll
+            for (int c = 0; c < CT; ++c) epilogue_tile(a.ep, acc[j][c], b);
+        }
+    }
     if constexpr (sizeof(TY) == 2) {
         if (a.out_bytes != 0) {
             // A 16-bit tile straight from the accumulators is 8 bytes per lane, 32-byte runs per

@@ -50,6 +50,18 @@ __device__ __forceinline__ void store_row(T *p, const float (&in)[VEC]) {
     }
 }
 
+// Epilogue on an accumulator tile of the MFMA kernels: lane 16 g + n holds 4 pixels of row
+// (first row of the stripe) + n.  A uniform test keeps the plain product free of it.
+__device__ __forceinline__ float epilogue_value(const Epilogue &e, float v, float b) {
+    return fminf(fmaxf(v + b, e.lo), e.hi);
+}
+__device__ __forceinline__ float epilogue_bias(const Epilogue &e, int row, int M) {
+    return (e.bias != nullptr && row < M) ? e.bias[row] : 0.f;
+}
+__device__ __forceinline__ void epilogue_tile(const Epilogue &e, float4v &acc, float b) {
+#pragma unroll
+    for (int v = 0; v < 4; ++v) acc[v] = epilogue_value(e, acc[v], b);
+}
 
 template <bool BF16>
 __device__ __forceinline__ float4v mfma16(short8v a, short8v b, float4v c) {

@@ -149,6 +149,11 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(TileArgs a) {
 #pragma unroll
     for (int i = 0; i < SM; ++i) {
         const int stripe = stripe0 + wm * SM + i;
+        if (a.ep.on) {
+            const float b = epilogue_bias(a.ep, stripe * kStripe + n, a.M);
+#pragma unroll
+            for (int c = 0; c < PN; ++c) epilogue_tile(a.ep, acc[i][c], b);
+        }
 #pragma unroll
         for (int c = 0; c < PN; ++c) {
             const int byte = (16 * c + 4 * g) * YS;

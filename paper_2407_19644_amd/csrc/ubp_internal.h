@@ -151,6 +151,15 @@ struct TileLayoutDev {
 };
 
 // ------------------------------------------------------------------ kernel arguments
+// What happens to an output value between the accumulator and the store: Y = act(acc + bias[row]),
+// in fp32, before the one rounding to Y's type.  on == 0: nothing.  The activation is a clamp to
+// [lo, hi] (ReLU: lo = 0, hi = +inf), taken with maxNum / minNum, so that a NaN becomes lo.
+struct Epilogue {
+    const float *bias; // device, M floats, or null
+    int on;
+    float lo, hi;
+};
+
 struct StripeArgs {
     const int32_t *rg_ptr;
     const int32_t *rg_order;
@@ -168,6 +177,7 @@ struct StripeArgs {
     int resident;            // the ring holds all of K: slots are never refilled, a consumer may walk several row groups
     int vec_ok;              // X and Y allow 16-byte vector access on every row
     uint32_t *err;           // set to nonzero when a bounded wait runs out
+    Epilogue ep;
 };
 
 struct BlkArgs {
@@ -187,6 +197,7 @@ struct BlkArgs {
     int n_producers;
     int out_bytes;           // LDS bytes per consumer for leaving 16-bit tiles as whole rows; 0: none
     uint32_t *err;
+    Epilogue ep;
 };
 
 struct TileArgs {
@@ -202,6 +213,7 @@ struct TileArgs {
     int kt_total;            // 32-column tiles per stripe in frags
     int skip;                // some tile keeps no weight: run the instantiation that tests the occupancy bits
     uint32_t *err;           // the handle's error flags (bounded waits that ran out)
+    Epilogue ep;
 };
 
 } // namespace ubp
@@ -255,7 +267,7 @@ ubp_status upload_tile_layout(const ubp_packed *p);
 // Launchers.  `dry` only raises the kernels' dynamic LDS limit on the current device (what a
 // first launch of a shape would do), so that a later launch is nothing but a launch.
 ubp_status launch_wros(const ubp_packed *p, const void *X, int64_t ldx, int N, void *Y, int64_t ldy, ubp_dtype y_dtype,
-                       int rpr, bool naive, void *stream, bool dry);
+                       int rpr, bool naive, const Epilogue &ep, void *stream, bool dry);
 ubp_status launch_stripe(const StripeArgs &a, bool bf16, bool y_f32, int G, int CT, int waves, void *stream, bool dry);
 int stripe_max_waves(int G, int CT);
 ubp_status launch_blk(const BlkArgs &a, bool bf16, bool y_f32, int G, int waves, void *stream, bool dry);

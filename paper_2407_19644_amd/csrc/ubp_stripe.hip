@@ -410,6 +410,11 @@ __global__ __launch_bounds__(stripe_max_threads(G, CT, D)) void stripe_kernel(St
         for (int j = 0; j < G; ++j) {
             const int row = (rg_done * G + j) * kStripe + n;
             if (row >= a.M) continue;
+            if (a.ep.on) {
+                const float b = epilogue_bias(a.ep, row, a.M);
+#pragma unroll
+                for (int c = 0; c < CT; ++c) epilogue_tile(a.ep, acc[j][c], b);
+            }
 #pragma unroll
             for (int c = 0; c < CT; ++c) {
                 const int px = col0 + 16 * c + 4 * g;

@@ -179,6 +179,11 @@ __global__ __launch_bounds__(512) void xstat_kernel(TileArgs a) {
         // after the detour an instruction writes whole rows of the block (RB bytes each).
         // 16-byte pieces of a row are XOR-swizzled by the row number so that the 16 lanes LDS
         // serves together hit 64 different banks on the way in and on the way out.
+        if (a.ep.on) {
+            const float b = epilogue_bias(a.ep, stripe * kStripe + n, a.M);
+#pragma unroll
+            for (int c = 0; c < CT; ++c) epilogue_tile(a.ep, acc[c], b);
+        }
         constexpr int RB = 16 * CT * (int)sizeof(TY);   // bytes per row: 64, 128 or 256
         constexpr int PR = RB / 16;                     // pieces per row
         constexpr int RP = 256 / RB;                    // rows per 256 bytes (one pass over the banks)
@@ -471,6 +476,11 @@ __global__ __launch_bounds__((kChunkStripes / SW + kChunkProducers) * 64) void x
 #pragma unroll
     for (int i = 0; i < SW; ++i) {
         const int stripe = s0 + i;
+        if (a.ep.on) {
+            const float b = epilogue_bias(a.ep, stripe * kStripe + n, a.M);
+#pragma unroll
+            for (int c = 0; c < CT; ++c) epilogue_tile(a.ep, acc[i][c], b);
+        }
 #pragma unroll
         for (int jp = 0; jp < NI; ++jp) {
             uint4v o;

@@ -18,7 +18,7 @@ namespace {
 template <typename TX, typename TY, int BH, int VEC>
 __global__ __launch_bounds__(256) void wros_kernel(const int32_t *__restrict__ indptr, const int32_t *__restrict__ indices,
                                                   const float *__restrict__ vals, const TX *__restrict__ X, int64_t ldx,
-                                                  TY *__restrict__ Y, int64_t ldy, int M, int N, int bw, int rpr) {
+                                                  TY *__restrict__ Y, int64_t ldy, int M, int N, int bw, int rpr, Epilogue ep) {
     const int col = (blockIdx.x * 256 + threadIdx.x) * VEC;
     if (col >= N) return;
     const int lo = blockIdx.y * rpr;
@@ -53,7 +53,14 @@ __global__ __launch_bounds__(256) void wros_kernel(const int32_t *__restrict__ i
                     }
                 }
             }
-            if (i >= lo) store_row<TY, VEC>(Y + (int64_t)i * ldy + col, acc[u]);
+            if (i >= lo) {
+                if (ep.on) {
+                    const float b = ep.bias ? ep.bias[i] : 0.f;
+#pragma unroll
+                    for (int v = 0; v < VEC; ++v) acc[u][v] = epilogue_value(ep, acc[u][v], b);
+                }
+                store_row<TY, VEC>(Y + (int64_t)i * ldy + col, acc[u]);
+            }
 #pragma unroll
             for (int v = 0; v < VEC; ++v) acc[u][v] = 0.f;
         }
@@ -69,7 +76,7 @@ __global__ __launch_bounds__(256) void wros_kernel(const int32_t *__restrict__ i
 template <typename TX, typename TY, int BH, int VEC>
 __global__ __launch_bounds__(256) void naive_kernel(const int32_t *__restrict__ indptr, const int32_t *__restrict__ indices,
                                                    const float *__restrict__ vals, const TX *__restrict__ X, int64_t ldx,
-                                                   TY *__restrict__ Y, int64_t ldy, int M, int N, int bw, int rpr) {
+                                                   TY *__restrict__ Y, int64_t ldy, int M, int N, int bw, int rpr, Epilogue ep) {
     const int col = (blockIdx.x * 256 + threadIdx.x) * VEC;
     if (col >= N) return;
     const int lo = blockIdx.y * rpr;
@@ -100,7 +107,14 @@ __global__ __launch_bounds__(256) void naive_kernel(const int32_t *__restrict__ 
                 }
             }
         }
-        if (i >= lo) store_row<TY, VEC>(Y + (int64_t)i * ldy + col, acc[0]);
+        if (i >= lo) {
+            if (ep.on) {
+                const float b = ep.bias ? ep.bias[i] : 0.f;
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) acc[0][v] = epilogue_value(ep, acc[0][v], b);
+            }
+            store_row<TY, VEC>(Y + (int64_t)i * ldy + col, acc[0]);
+        }
 #pragma unroll
         for (int t = 0; t + 1 < BH; ++t)
 #pragma unroll
@@ -112,13 +126,13 @@ __global__ __launch_bounds__(256) void naive_kernel(const int32_t *__restrict__ 
 
 template <typename TX, typename TY, int VEC>
 ubp_status launch_wros_bh(const ubp_packed *p, const void *X, int64_t ldx, int N, void *Y, int64_t ldy, int rpr,
-                          bool naive, hipStream_t st) {
+                          bool naive, const Epilogue &ep, hipStream_t st) {
     dim3 grid((unsigned)((N + 256 * VEC - 1) / (256 * VEC)), (unsigned)((p->M + rpr - 1) / rpr));
 #define UBP_WROS_CASE(BH)                                                                                              \
     case BH:                                                                                                           \
         hipLaunchKernelGGL((naive ? (naive_kernel<TX, TY, BH, VEC>) : (wros_kernel<TX, TY, BH, VEC>)), grid, dim3(256), 0, \
                            st, p->d_indptr, p->d_indices, p->d_values_f32, static_cast<const TX *>(X), ldx,           \
-                           static_cast<TY *>(Y), ldy, p->M, N, p->bw, rpr);                                            \
+                           static_cast<TY *>(Y), ldy, p->M, N, p->bw, rpr, ep);                                        \
         break;
     switch (p->bh) {
         UBP_WROS_CASE(1) UBP_WROS_CASE(2) UBP_WROS_CASE(3) UBP_WROS_CASE(4) UBP_WROS_CASE(5) UBP_WROS_CASE(6)
@@ -132,30 +146,30 @@ ubp_status launch_wros_bh(const ubp_packed *p, const void *X, int64_t ldx, int N
 
 template <typename TX, typename TY>
 ubp_status launch_wros_t(const ubp_packed *p, const void *X, int64_t ldx, int N, void *Y, int64_t ldy, int rpr,
-                         bool naive, hipStream_t st) {
+                         bool naive, const Epilogue &ep, hipStream_t st) {
     // 4 columns per thread when every row of X and Y can be accessed as an aligned 4-vector
     const bool vec = (N % 4 == 0) && (ldx % 4 == 0) && (ldy % 4 == 0) &&
                      (reinterpret_cast<uintptr_t>(X) % (4 * sizeof(TX)) == 0) &&
                      (reinterpret_cast<uintptr_t>(Y) % (4 * sizeof(TY)) == 0) && N >= 2048;
-    return vec ? launch_wros_bh<TX, TY, 4>(p, X, ldx, N, Y, ldy, rpr, naive, st)
-               : launch_wros_bh<TX, TY, 1>(p, X, ldx, N, Y, ldy, rpr, naive, st);
+    return vec ? launch_wros_bh<TX, TY, 4>(p, X, ldx, N, Y, ldy, rpr, naive, ep, st)
+               : launch_wros_bh<TX, TY, 1>(p, X, ldx, N, Y, ldy, rpr, naive, ep, st);
 }
 
 } // namespace
 
 ubp_status launch_wros(const ubp_packed *p, const void *X, int64_t ldx, int N, void *Y, int64_t ldy, ubp_dtype y_dtype,
-                       int rpr, bool naive, void *stream, bool dry) {
+                       int rpr, bool naive, const Epilogue &ep, void *stream, bool dry) {
     if (dry) return p->bh > 16 ? UBP_ERR_UNSUPPORTED : UBP_OK; // static LDS only: nothing to prepare
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (p->bh > 16) return UBP_ERR_UNSUPPORTED;
     switch (p->dtype) {
-    case UBP_F32: return launch_wros_t<float, float>(p, X, ldx, N, Y, ldy, rpr, naive, st);
+    case UBP_F32: return launch_wros_t<float, float>(p, X, ldx, N, Y, ldy, rpr, naive, ep, st);
     case UBP_F16:
-        return y_dtype == UBP_F32 ? launch_wros_t<_Float16, float>(p, X, ldx, N, Y, ldy, rpr, naive, st)
-                                  : launch_wros_t<_Float16, _Float16>(p, X, ldx, N, Y, ldy, rpr, naive, st);
+        return y_dtype == UBP_F32 ? launch_wros_t<_Float16, float>(p, X, ldx, N, Y, ldy, rpr, naive, ep, st)
+                                  : launch_wros_t<_Float16, _Float16>(p, X, ldx, N, Y, ldy, rpr, naive, ep, st);
     case UBP_BF16:
-        return y_dtype == UBP_F32 ? launch_wros_t<__bf16, float>(p, X, ldx, N, Y, ldy, rpr, naive, st)
-                                  : launch_wros_t<__bf16, __bf16>(p, X, ldx, N, Y, ldy, rpr, naive, st);
+        return y_dtype == UBP_F32 ? launch_wros_t<__bf16, float>(p, X, ldx, N, Y, ldy, rpr, naive, ep, st)
+                                  : launch_wros_t<__bf16, __bf16>(p, X, ldx, N, Y, ldy, rpr, naive, ep, st);
     }
     return UBP_ERR_INVALID_ARG;
 }

@@ -248,3 +248,19 @@ def test_planted_mistakes_fail_the_pins(worked_example):
     X = np.arange(1.0, 1 + K * 4).reshape(K, 4)
     Y = oracle.spmm(W, bh, bw, blocks, X)
     assert not np.array_equal(Y, W.T[:M, :K] @ X)
+
+
+def test_fused_epilogue_of_the_oracle():
+    """The epilogue function against hand values: bias goes by output ROW (a transposed bias, a
+    missing bias, relu before bias, swapped clamp bounds would all show), NaN becomes the lower
+    bound."""
+    Y = np.array([[1.0, -2.0, 0.5], [-1.0, 3.0, np.nan]])
+    b = np.array([0.25, -0.5])
+    assert np.array_equal(oracle.fused(Y), Y, equal_nan=True)
+    assert oracle.fused(Y, b)[:, :2].tolist() == [[1.25, -1.75], [-1.5, 2.5]]
+    assert oracle.fused(Y, b, "relu").tolist() == [[1.25, 0.0, 0.75], [0.0, 2.5, 0.0]]
+    assert oracle.fused(Y, b, "clamp", -1.0, 2.0).tolist() == [[1.25, -1.0, 0.75], [-1.0, 2.0, -1.0]]
+    assert oracle.fused(Y, None, "relu").tolist() == [[1.0, 0.0, 0.5], [0.0, 3.0, 0.0]]
+    assert oracle.fused(Y[1:], b, "relu", rows=[1]).tolist() == [[0.0, 2.5, 0.0]]
+    with pytest.raises(ValueError):
+        oracle.fused(Y, b, "clamp", 1.0, 0.0)

@@ -584,3 +584,82 @@ def test_selected_blocks_through_the_product(method):
         for y_dtype in sorted({dtype, "f32"}):
             Y = run_spmm(W, dtype, bh, bw, blocks, X, y_dtype)
             check(Y, Yref, Yabs, dtype, y_dtype)
+
+
+# ------------------------------------------------------------------ fused epilogue (bias, ReLU / clamp)
+def _run_fused(W, dtype, bh, bw, blocks, X, y_dtype, bias, activation, lo, hi, plan):
+    M = W.shape[0]
+    K, N = X.shape
+    p = ubp.pack(W, dtype, bh, bw, blocks, device=torch.cuda.current_device())
+    Xd = to_device(X, dtype)
+    tdt = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}[y_dtype]
+    Yd = torch.full((M, N), float("nan"), dtype=tdt, device="cuda")
+    bd = None if bias is None else torch.from_numpy(bias.astype(np.float32)).cuda()
+    ubp.spmm_fused(p, Xd.data_ptr(), N, N, Yd.data_ptr(), N, y_dtype, None if bd is None else bd.data_ptr(), activation, lo, hi,
+                   torch.cuda.current_stream().cuda_stream, plan)
+    torch.cuda.synchronize()
+    assert p.device_error() == 0
+    p.free()
+    t = Yd.cpu()
+    return decode_f64(t.view(torch.uint16).numpy(), "bf16") if y_dtype == "bf16" else t.numpy().astype(np.float64)
+
+
+FUSED_CASES = [  # kernel, (M, K, N, bh, bw, density), dtype
+    (1, (70, 45, 67, 3, 1, 0.4), "f32"), (1, (96, 300, 256, 4, 4, 0.25), "f16"), (3, (100, 300, 333, 8, 8, 0.2), "bf16"),
+    (2, (130, 600, 1000, 16, 16, 0.15), "bf16"), (2, (33, 40, 129, 5, 3, 0.3), "f16"),
+    (4, (200, 256, 328, 8, 8, 0.2), "f16"), (5, (160, 1024, 264, 4, 4, 0.25), "bf16"),
+    (6, (300, 2500, 192, 16, 32, 0.1), "bf16"), (6, (130, 600, 1000, 16, 16, 0.15), "f16"),
+    (7, (160, 320, 520, 4, 4, 0.45), "f16"), (0, (256, 2048, 128, 16, 16, 0.1), "bf16"), (0, (64, 64, 196, 4, 4, 0.5), "f32"),
+]
+
+
+@pytest.mark.parametrize("case", FUSED_CASES, ids=lambda c: "k%d-%s-%s" % (c[0], "x".join(map(str, c[1])), c[2]))
+def test_fused_epilogue(case):
+    """ubp_spmm_fused through every kernel: bias per output row, ReLU, clamp, bias alone, and the
+    empty epilogue (= the plain product, bit for bit), in both output types."""
+    kernel, (M, K, N, bh, bw, d), dtype = case
+    blocks, W, X = _layer(M, K, N, bh, bw, d, dtype, seed=3 * M + K)
+    Yref, Yabs = _oracle(W, dtype, bh, bw, blocks, X)
+    rng = np.random.default_rng(M + N)
+    scale = np.abs(Yref).max()
+    bias = (rng.standard_normal(M) * 0.5 * scale).astype(np.float32)      # fp32: what the library is given
+    plan = _plan(kernel=kernel) if kernel else None
+    for y_dtype in sorted({dtype, "f32"}):
+        plain = run_spmm(W, dtype, bh, bw, blocks, X, y_dtype, plan)
+        for b, act, lo, hi in ((bias, "relu", 0, 0), (bias, "clamp", -0.4 * scale, 0.7 * scale), (bias, None, 0, 0),
+                               (None, "relu", 0, 0), (None, None, 0, 0)):
+            Y = _run_fused(W, dtype, bh, bw, blocks, X, y_dtype, b, act, lo, hi, plan)
+            want = oracle.fused(Yref, None if b is None else b.astype(np.float64), act, lo, hi)
+            if b is None and act is None:
+                assert np.array_equal(Y, plain)
+                continue
+            # the bias is added to the fp32 accumulator: one more rounding of size |v| 2^-24
+            check(Y, want, None if Yabs is None else Yabs + np.abs(want) + (0 if b is None else np.abs(b)[:, None]), dtype, y_dtype)
+            if act == "relu":
+                assert (Y >= 0).all()
+            if act == "clamp" and y_dtype == "f32":                        # (a 16-bit Y rounds the bound itself)
+                assert (Y >= np.float32(lo)).all() and (Y <= np.float32(hi)).all()
+
+
+def test_fused_epilogue_arguments():
+    blocks, W, X = _layer(64, 64, 128, 4, 4, 0.3, "f16", seed=2)
+    with pytest.raises(ubp.UBPError) as e:
+        _run_fused(W, "f16", 4, 4, blocks, X, "f16", None, "clamp", 1.0, -1.0, None)     # lo > hi
+    assert e.value.code == 1
+    with pytest.raises(ubp.UBPError) as e:
+        _run_fused(W, "f16", 4, 4, blocks, X, "f16", None, "clamp", float("nan"), 1.0, None)
+    assert e.value.code == 1
+    # a NaN in the accumulator becomes the lower bound (IEEE maxNum), as the header says
+    Xn = decode_f64(X, "f16")
+    Xn[5, 7] = np.nan
+    Y = _run_fused(W, "f16", 4, 4, blocks, encode(Xn, "f16"), "f32", None, "relu", 0, 0, _plan(kernel=1))
+    assert np.isfinite(Y).all() and (Y >= 0).all()
+
+
+def test_fused_epilogue_full_layer():
+    """c4 at full size with bias + ReLU through the automatic choice, every element."""
+    cfg, blocks, W, X, Yref, Yabs = _full_reference("c4")
+    rng = np.random.default_rng(8)
+    bias = (rng.standard_normal(cfg.M) * 0.3 * np.abs(Yref).max()).astype(np.float32)
+    Y = _run_fused(W, cfg.dtype, cfg.bh, cfg.bw, blocks, X, cfg.dtype, bias, "relu", 0, 0, None)
+    check(Y, oracle.fused(Yref, bias.astype(np.float64), "relu"), None, cfg.dtype, cfg.dtype)
