@@ -329,14 +329,8 @@ __global__ __launch_bounds__(MAXT) void blk_kernel(BlkArgs a) {
     // ---- store: lane (g = lane/16, n = lane%16) holds pixels col0 + 16*c + 4*g + v of row
     // 16*(stripe0 + j) + n, j < stripes.  Rows no block touches are stored as zeros like any other.
     TY *Yt = static_cast<TY *>(a.Y);
-    if (a.ep.on) {
-#pragma unroll
-        for (int j = 0; j < G; ++j) {
-            const float b = epilogue_bias(a.ep, (stripe0 + j) * kStripe + n, a.M);
-#pragma unroll
-            for (int c = 0; c < CT; ++c) epilogue_tile(a.ep, acc[j][c], b);
-        }
-    }
+    // the epilogue (bias of the lane's row, clamp) is applied tile by tile on the way out
+    const bool fused = a.ep.on != 0;
     if constexpr (sizeof(TY) == 2) {
         if (a.out_bytes != 0) {
             // A 16-bit tile straight from the accumulators is 8 bytes per lane, 32-byte runs per
@@ -351,10 +345,12 @@ __global__ __launch_bounds__(MAXT) void blk_kernel(BlkArgs a) {
 #pragma unroll
             for (int j = 0; j < G; ++j) {
                 if (j >= stripes) break;
+                const float bj = fused ? epilogue_bias(a.ep, (stripe0 + j) * kStripe + n, a.M) : 0.f;
 #pragma unroll
                 for (int c = 0; c < CT; ++c) {
                     typedef TY ty4 __attribute__((ext_vector_type(4)));
                     ty4 o;
+                    if (fused) epilogue_tile(a.ep, acc[j][c], bj);
 #pragma unroll
                     for (int v = 0; v < 4; ++v) o[v] = from_f32<TY>(acc[j][c][v]);
                     const int piece = (2 * c + (g >> 1)) ^ ((n / RP) & (PR - 1));
@@ -375,10 +371,12 @@ __global__ __launch_bounds__(MAXT) void blk_kernel(BlkArgs a) {
     for (int j = 0; j < G; ++j) {
         const int row = (stripe0 + j) * kStripe + n;
         if (j >= stripes || row >= a.M) continue;
+        const float bj = fused ? epilogue_bias(a.ep, row, a.M) : 0.f;
 #pragma unroll
         for (int c = 0; c < CT; ++c) {
             const int px = col0 + 16 * c + 4 * g;
             TY *dst = Yt + (int64_t)row * a.ldy + px;
+            if (fused) epilogue_tile(a.ep, acc[j][c], bj);
             float v[4] = {acc[j][c][0], acc[j][c][1], acc[j][c][2], acc[j][c][3]};
             store_row<TY, 4>(dst, v);
         }
