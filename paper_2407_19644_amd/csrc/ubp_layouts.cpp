@@ -311,7 +311,7 @@ void build_blk(const ubp_packed *p, BlkLayout &L, int G) {
     const int M = p->M, K = p->K, bh = p->bh, bw = p->bw;
     constexpr int CT = 4;
     const int R = ring_slots(CT);
-    const int pair_span = R / 2 - 2; // chunks two halves of a step may lie apart
+    const int pair_span = R / 2; // chunks two halves of a step may lie apart (a wavefront then holds at most R / 2 + 2)
     L.G = G;
     L.rg_first = cut_row_groups(p, G);
     L.nrg = (int)L.rg_first.size() - 1;
