@@ -261,6 +261,12 @@ __global__ __launch_bounds__(MAXT) void blk_kernel(BlkArgs a) {
         // loads it believes pending on registers that the loop body writes would otherwise cost a
         // wait for everything in flight at the first step of every round of the loop
         __builtin_amdgcn_s_waitcnt(0x0f70);
+        {
+            // nothing below the first step's windows is ever read: say so before the first wait, or
+            // a row group whose first block lies beyond the ring would hold the producers back
+            const uint32_t first = __builtin_amdgcn_readlane(mcur[0], 0);
+            release_upto((int)(min(first & 0xffffu, first >> 16) >> 6));
+        }
         int li = 0; // index of the round's first step within the metadata block
         for (int s = s_first; s < s_all; s += D) {
             if (li == 64) {
