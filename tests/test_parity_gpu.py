@@ -193,7 +193,7 @@ def test_automatic_kernel_choice():
 BLOCK_SHAPES = [(130, 600, 1000, 16, 16, 0.15), (100, 300, 328, 8, 8, 0.2), (96, 700, 256, 4, 4, 0.25), (33, 40, 136, 5, 3, 0.3),
                 (70, 45, 72, 3, 1, 0.4), (16, 16, 64, 16, 16, 1.0), (257, 31, 104, 1, 1, 0.3), (300, 2500, 192, 16, 32, 0.1),
                 (150, 1300, 136, 16, 40, 0.2), (200, 3000, 64, 12, 16, 0.1), (64, 16, 200, 16, 16, 0.25),
-                (160, 4096, 64, 16, 16, 0.004), (400, 6000, 128, 16, 16, 0.002)]   # row groups whose first block lies beyond the ring
+                (160, 4096, 64, 16, 16, 0.004), (400, 6000, 128, 16, 16, 0.002), (64, 8192, 64, 16, 16, 0.0005)]   # row groups whose first block lies beyond the ring
 
 
 @pytest.mark.parametrize("shape", BLOCK_SHAPES, ids=lambda s: "x".join(map(str, s)))
