@@ -401,3 +401,14 @@ def test_benchmark_layer_layouts_decode_to_the_dense_matrix(cfg):
     if cfg.name != "c4":                                 # (c4's zero-filled matrix would be 32 MB: not built)
         assert np.array_equal(_decode_tiles(p, cfg.M, cfg.K)[0], dense_bits)
     p.free()
+
+
+def test_benchmark_refuses_more_than_one_gpu():
+    """The product path runs on exactly one GPU: asking the benchmark for more ends with a message
+    and a non-zero status before anything touches a device."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    res = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], stdout=subprocess.PIPE,
+                         stderr=subprocess.PIPE, text=True, timeout=120)
+    assert res.returncode != 0 and "one GPU" in res.stderr and res.stdout.strip() == ""
