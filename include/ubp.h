@@ -155,10 +155,13 @@ ubp_status ubp_spmm(const ubp_packed *p, const void *X_dev, int64_t ldx, int32_t
  *                (waves 1..8 share a slice's stripes).
  *                5 (any K whose zero-filled W stays below 8 MB) cuts K into chunks of 128 rows
  *                that pass through LDS and the registers while the accumulators of 16 stripes
- *                stay (sub_stripes 2 or 4 = stripes per multiplying wavefront; waves fixed).
+ *                stay (sub_stripes 2 or 4 = stripes per multiplying wavefront; waves fixed; by
+ *                itself 4, or 2 with twice the slices where the workgroups would fill less than
+ *                half the CUs).
  *                6 = MFMA kernel with whole blocks as operands, stored by row modulo 16 - the
  *                paper's rotation with period 16 (f16 / bf16, bh <= 16, 16 <= K < 65408, N >= 64,
- *                16-byte aligned rows; col_tiles 4 only; sub_stripes 2, 4 or 5).
+ *                16-byte aligned rows; col_tiles 4 only; sub_stripes 2, 4 or 5 = the most stripes a
+ *                wavefront's row group may have: row groups are cut shorter where many blocks start).
  *                7 = MFMA kernel on the same operand tiles with BOTH operands staged in LDS: a
  *                workgroup owns up to 256 rows x 256 pixels of Y for the whole of K (f16 / bf16,
  *                same alignment as 4 and 5; only for matrices whose every tile keeps a weight;
@@ -167,8 +170,7 @@ ubp_status ubp_spmm(const ubp_packed *p, const void *X_dev, int64_t ldx, int32_t
  *                about one workgroup per CU).
  *                0 picks 1 for fp32; 6 for 16-row blocks at least 16 wide when K > 1024; else, while
  *                at least half of the 16 x 32 tiles of W keep a weight, 7 (every tile keeps one, and
- *                K <= 256 or N <= 4096), 4 (K <= 256) or 5; else 2.
- *                (3 is not used.)
+ *                K <= 256 or N <= 4096), 4 (K <= 256) or 5; else 2.  (3 is never picked.)
  *   sub_stripes: kernels 2 and 6, 16-row stripes per wavefront (1, 2 or 4; kernel 6: 2, 4 or 5,
  *                by itself 5 where that saves a workgroup row, else 4);
  *                kernel 5: 2 or 4.
